@@ -1,0 +1,161 @@
+/*
+ * gvq.h -- C ABI of libgvq: the GradiVeQ slice-wise linear PCA gradient codec for
+ * AMD MI355X (gfx950).
+ *
+ * Notation.  A flattened gradient of M numbers is cut into S = ceil(M/d) slices of d
+ * adjacent numbers (the paper's slice size K); each slice is projected onto k basis
+ * vectors (the paper's d), so the compression ratio is d/k.  N is the number of workers
+ * whose gradients are summed, L the number of gradients a basis is fitted on (the
+ * paper's L_t).  A "basis" is the triple (U, mu, eig): U is d x k with orthonormal
+ * columns, mu the length-d whitening vector, eig the d eigenvalues of the sample
+ * covariance in decreasing order.  A gradient may be covered by several bases: basis b
+ * serves the contiguous slice range [block_slice_offsets[b], block_slice_offsets[b+1]).
+ *
+ * Conventions for every entry point
+ *   - return value: 0 (GVQ_OK) or a negative gvq_status_t; nothing throws or aborts;
+ *   - "device" pointers are HIP device memory on the device that was current when the
+ *     handle was created, owned by the caller, 16-byte aligned (else GVQ_EALIGN);
+ *     "host" pointers are ordinary host memory, read or written before the call returns;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  fit, compress,
+ *     aggregate and decompress only enqueue kernels on it and never synchronise the device;
+ *     buffers must stay valid until that work has finished;
+ *   - the library owns the handle and the scratch memory inside it (allocated by
+ *     gvq_basis_create, released by gvq_basis_destroy) and nothing else;
+ *   - calls on one handle must not overlap in time on different streams.
+ *
+ * Layouts
+ *   gradient    : M elements, fp32 or bf16 (bit pattern in 16 bits), slice j = elements
+ *                 [j*d, j*d+d); the last slice may be partial and is treated as zero-padded;
+ *   compressed  : float [S][k], slice-major, so any range of slices is one contiguous
+ *                 byte range (what a ring all-reduce segment needs);
+ *   U           : float [B][d][k] row-major (B = number of bases);  mu: float [B][d];
+ *   eig, cov    : double [B][d], double [B][d][d].
+ */
+#ifndef GVQ_H
+#define GVQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gvq_basis gvq_basis_t; /* opaque */
+
+typedef enum { GVQ_F32 = 0, GVQ_BF16 = 1 } gvq_dtype_t;
+
+typedef enum {
+    GVQ_OK = 0,
+    GVQ_EINVAL = -1,     /* null pointer, size or count out of range, bad block offsets */
+    GVQ_EALIGN = -2,     /* a device pointer is not 16-byte aligned */
+    GVQ_ENOTFIT = -3,    /* compress / decompress / export before fit or import */
+    GVQ_EHIP = -4,       /* a HIP call failed; gvq_strerror gives the HIP text */
+    GVQ_ENOMEM = -5,     /* host or device allocation failed */
+    GVQ_ENONFINITE = -6, /* gvq_fit_status: a fitted eigenvalue is NaN or Inf */
+    GVQ_ENOCONV = -7     /* gvq_fit_status: the eigensolver hit its sweep limit */
+} gvq_status_t;
+
+#define GVQ_MAX_D 128 /* largest supported slice length */
+
+/*
+ * Create the codec state for gradients of n_elems (M >= 1) elements of grad_dtype, slice
+ * length d in [2, GVQ_MAX_D], k in [1, d] kept components (the paper requires k < d; k = d
+ * is accepted and makes the codec lossless).  block_slice_offsets: host array of
+ * n_blocks+1 strictly increasing slice indices, first 0, last S; NULL means one basis for
+ * the whole gradient (n_blocks must then be 1).  Allocates the device copies of U, mu,
+ * eig and the fit scratch on the current device.  Section 2 (slicing; one compressor per
+ * group of slices, Section 3 "compressor reuse").
+ */
+int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blocks,
+                     const int64_t* block_slice_offsets, gvq_dtype_t grad_dtype);
+
+/* Release the handle and its device memory.  Synchronises the device first. NULL is OK. */
+int gvq_basis_destroy(gvq_basis_t* h);
+
+/* S = ceil(M/d), or GVQ_EINVAL for a NULL handle. */
+int64_t gvq_num_slices(const gvq_basis_t* h);
+
+/*
+ * Basis refresh (Section 2, PCA paragraph after Eq. 4).  grads: host array of L >= 1
+ * device pointers, each a gradient of M elements of the handle's dtype; they are taken
+ * as samples of the *aggregated* gradient.  For every basis b the sample set is every
+ * full slice of its range in each of the L gradients (a partial tail slice is not a
+ * sample): mu_b = sample mean, C_b = covariance with normaliser 1/n, accumulated in
+ * float64 from exact products; C_b is eigendecomposed in float64 (Jacobi rotations),
+ * eigenvalues sorted in decreasing order, U_b = eigenvectors of the k largest, each
+ * negated if needed so that its largest-magnitude entry (lowest index on ties) is
+ * positive.  Results stay on the device inside the handle.  A basis whose range holds
+ * no full slice gets mu = 0, eig = 0 and U = the first k unit vectors.
+ * Asynchronous on `stream`; the handle counts as fitted once this returns GVQ_OK.
+ */
+int gvq_fit_basis(gvq_basis_t* h, const void* const* grads, int L, void* stream);
+
+/*
+ * Waits for `stream`'s work, then reports on the last fit: *max_sweeps (may be NULL)
+ * receives the largest Jacobi sweep count over the bases.  Returns GVQ_ENOCONV if a basis
+ * hit the sweep limit, GVQ_ENONFINITE if an eigenvalue is not finite (e.g. NaN/Inf in a
+ * fit gradient), GVQ_ENOTFIT if no fit was run.
+ */
+int gvq_fit_status(const gvq_basis_t* h, int* max_sweeps, void* stream);
+
+/*
+ * Eq. (2): comp_out[j][:] = U_b^T (x_j - mu_b / n_workers) for every slice j of `grad`
+ * (device, M elements of the handle's dtype), b the basis of slice j, the tail slice
+ * zero-padded.  comp_out: device float [S][k].  n_workers >= 1 must equal the number of
+ * vectors later summed by gvq_aggregate (only then do the mu/N terms add up to mu, Eq. 3);
+ * the library cannot check this.  fp32 arithmetic, fp32 accumulation.
+ */
+int gvq_compress(const gvq_basis_t* h, const void* grad, int n_workers, float* comp_out,
+                 void* stream);
+
+/*
+ * Eq. (3): comp_sum = comps[0] + comps[1] + ... + comps[N-1], element-wise over S*k
+ * floats, added in that order in fp32.  comps: host array of N >= 1 device pointers.
+ * comp_sum may alias comps[0] only.
+ */
+int gvq_aggregate(const gvq_basis_t* h, const float* const* comps, int N, float* comp_sum,
+                  void* stream);
+
+/*
+ * Eq. (4): grad_out[j*d + e] = (U_b comp_sum[j][:])[e] + mu_b[e], for the first M elements.
+ * grad_out: device, M elements of out_dtype (bf16 is rounded to nearest even).
+ */
+int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out,
+                   gvq_dtype_t out_dtype, void* stream);
+
+/*
+ * Copy the basis to host arrays (any may be NULL): U float [B][d][k], mu float [B][d],
+ * eig double [B][d].  Synchronises the device.  eig is all zero after gvq_basis_import.
+ */
+int gvq_basis_export(const gvq_basis_t* h, float* U, float* mu, double* eig);
+
+/*
+ * Host copy of the covariance matrices of the last fit, double [B][d][d] (what the
+ * eigensolver was given), and of the per-basis sample counts int64 [B] (either may be
+ * NULL).  Synchronises the device.  GVQ_ENOTFIT unless gvq_fit_basis ran on this handle.
+ */
+int gvq_basis_export_cov(const gvq_basis_t* h, double* cov, int64_t* n_samples);
+
+/*
+ * Replace the basis by host arrays U float [B][d][k] and mu float [B][d] (checkpoint
+ * restore; also lets a test inject a basis).  U is used as given: no orthonormality check.
+ * Synchronous.
+ */
+int gvq_basis_import(gvq_basis_t* h, const float* U, const float* mu);
+
+/*
+ * Text for a status code.  For GVQ_EHIP the text includes the message of the most recent
+ * failed HIP call in this process.  The pointer stays valid until the next call.
+ */
+const char* gvq_strerror(int status);
+
+/*
+ * Launch tuning (benchmarks only): option 0 = workgroups per compute unit for the
+ * streaming kernels (0 restores the default).  Returns GVQ_EINVAL for unknown options.
+ */
+int gvq_set_option(int option, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GVQ_H */
