@@ -25,7 +25,9 @@
  *     here by the classical cyclic Jacobi rotation method run to convergence;
  *   - each kept eigenvector is negated if needed so that its entry of largest
  *     magnitude (lowest index on ties) is positive;
- *   - one mu and one U per basis, shared by all slices of the basis' range.
+ *   - one mu and one U per basis, shared by all slices of the basis' range;
+ *   - a basis with no sample (its range holds only the partial tail slice) has mu = 0,
+ *     eigenvalues 0 and the first k unit vectors as U.
  *
  * Every floating-point value is widened to double on load (fp32 and bf16 widen
  * exactly) and every operation is done in double.  Loops over slices are split over
@@ -298,7 +300,9 @@ int gvq_oracle_basis_from_cov(const double *C, int d, int k, double *U, double *
 /* ------------------------------------------------------------------------------------
  * Basis refresh for every block: block b covers slices [offs[b], offs[b+1]).
  * U[B][d][k], mu[B][d], eig[B][d], optional C_out[B][d][d] (may be NULL).
- * Returns 0, or -1 if an eigensolve did not converge, or -2 if a block has no sample.
+ * A block whose range holds no full slice has no sample: its mean and covariance are
+ * taken as zero, so its eigenvectors are the unit vectors and U is the first k of them.
+ * Returns 0, or -1 if an eigensolve did not converge.
  * ---------------------------------------------------------------------------------- */
 int gvq_oracle_fit(const void *const *grads, int L, int64_t M, int d, int k, int dtype,
                    int n_blocks, const int64_t *offs, double *U, double *mu, double *eig,
@@ -307,9 +311,7 @@ int gvq_oracle_fit(const void *const *grads, int L, int64_t M, int d, int k, int
     double *C = (double *)malloc(sizeof(double) * d * d);
     int rc = 0;
     for (int b = 0; b < n_blocks; ++b) {
-        int64_t n = gvq_oracle_moments(grads, L, M, d, dtype, offs[b], offs[b + 1],
-                                       mu + (size_t)b * d, C);
-        if (n == 0) rc = -2;
+        gvq_oracle_moments(grads, L, M, d, dtype, offs[b], offs[b + 1], mu + (size_t)b * d, C);
         if (C_out) memcpy(C_out + (size_t)b * d * d, C, sizeof(double) * d * d);
         int sw = gvq_oracle_basis_from_cov(C, d, k, U + (size_t)b * d * k, eig + (size_t)b * d);
         if (sw < 0 && rc == 0) rc = -1;

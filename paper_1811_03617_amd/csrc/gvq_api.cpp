@@ -1,0 +1,248 @@
+// C ABI of libgvq: argument checking, handle life cycle, host<->device copies of the basis.
+// All arithmetic of the codec runs in the HIP kernels (gvq_codec.hip, gvq_fit.hip).
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "gvq_internal.h"
+
+static thread_local char g_hip_msg[256] = "no HIP error recorded";
+static thread_local char g_msg[320];
+static int g_wg_per_cu = 0;
+
+int gvq_hip_fail(hipError_t e, const char* what)
+{
+    snprintf(g_hip_msg, sizeof g_hip_msg, "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();  // clear the sticky error
+    return GVQ_EHIP;
+}
+
+int gvq_opt_wg_per_cu() { return g_wg_per_cu; }
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+extern "C" {
+
+const char* gvq_strerror(int status)
+{
+    switch (status) {
+    case GVQ_OK: return "ok";
+    case GVQ_EINVAL: return "invalid argument";
+    case GVQ_EALIGN: return "device pointer is not 16-byte aligned";
+    case GVQ_ENOTFIT: return "basis not fitted or imported";
+    case GVQ_EHIP:
+        snprintf(g_msg, sizeof g_msg, "HIP call failed (%s)", g_hip_msg);
+        return g_msg;
+    case GVQ_ENOMEM: return "out of memory";
+    case GVQ_ENONFINITE: return "fit produced a non-finite eigenvalue";
+    case GVQ_ENOCONV: return "eigensolver did not converge";
+    default: return "unknown status";
+    }
+}
+
+int gvq_set_option(int option, int value)
+{
+    if (option == 0 && value >= 0 && value <= 64) { g_wg_per_cu = value; return GVQ_OK; }
+    return GVQ_EINVAL;
+}
+
+int gvq_basis_destroy(gvq_basis_t* h)
+{
+    if (!h) return GVQ_OK;
+    (void)hipDeviceSynchronize();
+    void* dev[] = {h->d_offs, h->d_U, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_mom, h->d_sweeps};
+    for (void* p : dev)
+        if (p) (void)hipFree(p);
+    free(h->h_offs);
+    delete h;
+    (void)hipGetLastError();
+    return GVQ_OK;
+}
+
+int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blocks,
+                     const int64_t* offs, gvq_dtype_t dtype)
+{
+    if (!out) return GVQ_EINVAL;
+    *out = nullptr;
+    if (n_elems < 1 || d < 2 || d > GVQ_MAX_D || k < 1 || k > d || n_blocks < 1) return GVQ_EINVAL;
+    if (dtype != GVQ_F32 && dtype != GVQ_BF16) return GVQ_EINVAL;
+    const int64_t S = (n_elems + d - 1) / d;
+    if (!offs && n_blocks != 1) return GVQ_EINVAL;
+    if (offs) {
+        if (n_blocks > S || offs[0] != 0 || offs[n_blocks] != S) return GVQ_EINVAL;
+        for (int b = 0; b < n_blocks; ++b)
+            if (offs[b + 1] <= offs[b]) return GVQ_EINVAL;
+    }
+    gvq_basis* h = new (std::nothrow) gvq_basis();
+    if (!h) return GVQ_ENOMEM;
+    h->M = n_elems; h->S = S; h->d = d; h->k = k; h->B = n_blocks; h->dtype = dtype;
+    h->h_offs = (int64_t*)malloc(sizeof(int64_t) * (n_blocks + 1));
+    if (!h->h_offs) { delete h; return GVQ_ENOMEM; }
+    if (offs) memcpy(h->h_offs, offs, sizeof(int64_t) * (n_blocks + 1));
+    else { h->h_offs[0] = 0; h->h_offs[1] = S; }
+
+    // moment partials per basis: enough workgroups to fill the chip, never more than one
+    // per 64 sample slices of the largest basis
+    int64_t longest = 0;
+    for (int b = 0; b < n_blocks; ++b)
+        if (h->h_offs[b + 1] - h->h_offs[b] > longest) longest = h->h_offs[b + 1] - h->h_offs[b];
+
+    int rc = GVQ_OK;
+    hipError_t e;
+#define TRY(call) do { e = (call); if (e != hipSuccess) { rc = gvq_hip_fail(e, #call); goto fail; } } while (0)
+    {
+        hipDeviceProp_t prop;
+        TRY(hipGetDevice(&h->device));
+        TRY(hipGetDeviceProperties(&prop, h->device));
+        h->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        int64_t P = (4LL * h->num_cu + n_blocks - 1) / n_blocks;
+        if (P > (longest + 63) / 64) P = (longest + 63) / 64;
+        if (P < 1) P = 1;
+        h->P = (int)P;
+        const size_t B = (size_t)n_blocks, W = (size_t)d * d + d, n = (size_t)(d + (d & 1));
+        TRY(hipMalloc((void**)&h->d_offs, sizeof(int64_t) * (B + 1)));
+        TRY(hipMalloc((void**)&h->d_U, sizeof(float) * B * d * k));
+        TRY(hipMalloc((void**)&h->d_mu, sizeof(float) * B * d));
+        TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
+        TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
+        TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
+        TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * W));
+        TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
+        TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
+        TRY(hipMemcpy(h->d_offs, h->h_offs, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
+        TRY(hipMemset(h->d_eig, 0, sizeof(double) * B * d));
+    }
+#undef TRY
+    *out = h;
+    return GVQ_OK;
+fail:
+    gvq_basis_destroy(h);
+    return rc;
+}
+
+int64_t gvq_num_slices(const gvq_basis_t* h) { return h ? h->S : (int64_t)GVQ_EINVAL; }
+
+int gvq_fit_basis(gvq_basis_t* h, const void* const* grads, int L, void* stream)
+{
+    if (!h || !grads || L < 1) return GVQ_EINVAL;
+    for (int l = 0; l < L; ++l) {
+        if (!grads[l]) return GVQ_EINVAL;
+        if (!aligned16(grads[l])) return GVQ_EALIGN;
+    }
+    int rc = gvq_launch_fit(h, grads, L, (hipStream_t)stream);
+    if (rc != GVQ_OK) return rc;
+    h->fitted = true;
+    h->has_cov = true;
+    h->fit_L = L;
+    return GVQ_OK;
+}
+
+int gvq_fit_status(const gvq_basis_t* h, int* max_sweeps, void* stream)
+{
+    if (!h) return GVQ_EINVAL;
+    if (!h->has_cov) return GVQ_ENOTFIT;
+    GVQ_HIP(hipStreamSynchronize((hipStream_t)stream));
+    const size_t B = (size_t)h->B;
+    int* sw = (int*)malloc(sizeof(int) * B);
+    double* eig = (double*)malloc(sizeof(double) * B * h->d);
+    if (!sw || !eig) { free(sw); free(eig); return GVQ_ENOMEM; }
+    hipError_t e1 = hipMemcpy(sw, h->d_sweeps, sizeof(int) * B, hipMemcpyDeviceToHost);
+    hipError_t e2 = hipMemcpy(eig, h->d_eig, sizeof(double) * B * h->d, hipMemcpyDeviceToHost);
+    int rc = GVQ_OK;
+    if (e1 != hipSuccess) rc = gvq_hip_fail(e1, "hipMemcpy(sweeps)");
+    else if (e2 != hipSuccess) rc = gvq_hip_fail(e2, "hipMemcpy(eig)");
+    else {
+        int mx = 0;
+        bool noconv = false, nonfinite = false;
+        for (size_t b = 0; b < B; ++b) {
+            if (sw[b] < 0) noconv = true;
+            else if (sw[b] > mx) mx = sw[b];
+        }
+        for (size_t i = 0; i < B * h->d; ++i)
+            if (!isfinite(eig[i])) nonfinite = true;
+        if (max_sweeps) *max_sweeps = mx;
+        if (nonfinite) rc = GVQ_ENONFINITE;
+        else if (noconv) rc = GVQ_ENOCONV;
+    }
+    free(sw); free(eig);
+    return rc;
+}
+
+int gvq_compress(const gvq_basis_t* h, const void* grad, int n_workers, float* comp_out, void* stream)
+{
+    if (!h || !grad || !comp_out || n_workers < 1) return GVQ_EINVAL;
+    if (!aligned16(grad) || !aligned16(comp_out)) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    return gvq_launch_compress(h, grad, n_workers, comp_out, (hipStream_t)stream);
+}
+
+int gvq_aggregate(const gvq_basis_t* h, const float* const* comps, int N, float* comp_sum, void* stream)
+{
+    if (!h || !comps || !comp_sum || N < 1) return GVQ_EINVAL;
+    if (!aligned16(comp_sum)) return GVQ_EALIGN;
+    for (int n = 0; n < N; ++n) {
+        if (!comps[n]) return GVQ_EINVAL;
+        if (!aligned16(comps[n])) return GVQ_EALIGN;
+        if (n > 0 && comps[n] == comp_sum) return GVQ_EINVAL;  // only comps[0] may alias the output
+    }
+    return gvq_launch_aggregate(h, comps, N, comp_sum, (hipStream_t)stream);
+}
+
+int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out, gvq_dtype_t out_dtype,
+                   void* stream)
+{
+    if (!h || !comp_sum || !grad_out) return GVQ_EINVAL;
+    if (out_dtype != GVQ_F32 && out_dtype != GVQ_BF16) return GVQ_EINVAL;
+    if (!aligned16(comp_sum) || !aligned16(grad_out)) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    return gvq_launch_decompress(h, comp_sum, grad_out, out_dtype, (hipStream_t)stream);
+}
+
+int gvq_basis_export(const gvq_basis_t* h, float* U, float* mu, double* eig)
+{
+    if (!h) return GVQ_EINVAL;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    GVQ_HIP(hipDeviceSynchronize());
+    const size_t B = (size_t)h->B;
+    if (U) GVQ_HIP(hipMemcpy(U, h->d_U, sizeof(float) * B * h->d * h->k, hipMemcpyDeviceToHost));
+    if (mu) GVQ_HIP(hipMemcpy(mu, h->d_mu, sizeof(float) * B * h->d, hipMemcpyDeviceToHost));
+    if (eig) GVQ_HIP(hipMemcpy(eig, h->d_eig, sizeof(double) * B * h->d, hipMemcpyDeviceToHost));
+    return GVQ_OK;
+}
+
+int gvq_basis_export_cov(const gvq_basis_t* h, double* cov, int64_t* n_samples)
+{
+    if (!h) return GVQ_EINVAL;
+    if (!h->has_cov) return GVQ_ENOTFIT;
+    GVQ_HIP(hipDeviceSynchronize());
+    const size_t B = (size_t)h->B;
+    if (cov) GVQ_HIP(hipMemcpy(cov, h->d_cov, sizeof(double) * B * h->d * h->d, hipMemcpyDeviceToHost));
+    if (n_samples) {
+        const int64_t full = h->M / h->d;
+        for (size_t b = 0; b < B; ++b) {
+            int64_t hi = h->h_offs[b + 1] < full ? h->h_offs[b + 1] : full;
+            int64_t cnt = hi > h->h_offs[b] ? hi - h->h_offs[b] : 0;
+            n_samples[b] = cnt * h->fit_L;
+        }
+    }
+    return GVQ_OK;
+}
+
+int gvq_basis_import(gvq_basis_t* h, const float* U, const float* mu)
+{
+    if (!h || !U || !mu) return GVQ_EINVAL;
+    GVQ_HIP(hipDeviceSynchronize());
+    const size_t B = (size_t)h->B;
+    GVQ_HIP(hipMemcpy(h->d_U, U, sizeof(float) * B * h->d * h->k, hipMemcpyHostToDevice));
+    GVQ_HIP(hipMemcpy(h->d_mu, mu, sizeof(float) * B * h->d, hipMemcpyHostToDevice));
+    GVQ_HIP(hipMemset(h->d_eig, 0, sizeof(double) * B * h->d));
+    GVQ_HIP(hipDeviceSynchronize());
+    h->fitted = true;
+    h->has_cov = false;
+    return GVQ_OK;
+}
+
+}  // extern "C"

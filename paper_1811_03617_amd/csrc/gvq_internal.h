@@ -1,0 +1,55 @@
+// Internal declarations shared by the translation units of libgvq (host side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gvq.h"
+
+#define GVQ_MAX_PTRS 32  // device pointers passed by value in one kernel launch
+
+struct gvq_basis {
+    int64_t M = 0, S = 0;       // elements, slices
+    int d = 0, k = 0, B = 0;    // slice length, kept components, number of bases
+    gvq_dtype_t dtype = GVQ_F32;
+    int device = 0;
+    int num_cu = 0;
+    int64_t* h_offs = nullptr;  // host [B+1]
+    int64_t* d_offs = nullptr;  // device [B+1]
+    float* d_U = nullptr;       // [B][d][k]
+    float* d_mu = nullptr;      // [B][d]
+    double* d_eig = nullptr;    // [B][d]
+    double* d_cov = nullptr;    // [B][d][d]
+    double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
+    double* d_part = nullptr;   // [B][P][d*d+d] per-workgroup moment partials
+    double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
+    int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
+    int P = 0;                  // moment partials per basis
+    int fit_L = 0;              // gradients of the last fit
+    bool fitted = false;        // basis usable (fit or import)
+    bool has_cov = false;       // d_cov / d_eig hold a fit's results
+};
+
+struct gvq_ptrs {
+    const void* p[GVQ_MAX_PTRS];
+};
+
+// Records the HIP error text for gvq_strerror and returns GVQ_EHIP.
+int gvq_hip_fail(hipError_t e, const char* what);
+
+#define GVQ_HIP(call)                                         \
+    do {                                                      \
+        hipError_t e__ = (call);                              \
+        if (e__ != hipSuccess) return gvq_hip_fail(e__, #call); \
+    } while (0)
+
+// Workgroups per compute unit for the streaming kernels (0 = pick from occupancy).
+int gvq_opt_wg_per_cu();
+
+// Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
+int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out,
+                        hipStream_t st);
+int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, float* out,
+                         hipStream_t st);
+int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt,
+                          hipStream_t st);
+int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st);

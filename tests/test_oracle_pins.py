@@ -283,3 +283,13 @@ def test_bf16_inputs_widen_exactly():
     U, mu, _ = oracle.fit([bits], 16, 4, dtype="bf16")
     np.testing.assert_array_equal(oracle.compress(bits, U, mu, 3, dtype="bf16"),
                                   oracle.compress(as_f32, U, mu, 3, dtype="f32"))
+
+
+def test_block_with_no_full_slice_gets_unit_vectors():
+    d, k = 8, 3
+    rng = np.random.default_rng(1)
+    M = 8 * 10 + 3
+    fitg = _rng_grads(rng, 2, M)
+    U, mu, eig = oracle.fit(fitg, d, k, offsets=[0, 10, 11])
+    np.testing.assert_array_equal(U[1], np.eye(d, k))
+    assert np.all(mu[1] == 0) and np.all(eig[1] == 0)
