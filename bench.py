@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the GradiVeQ codec hot path on one MI355X.
+
+One "step" = the whole compressed aggregation of one training iteration (Section 2,
+Eqs. 2-4): N x gvq_compress (one per simulated worker), gvq_aggregate, gvq_decompress, on
+synthetic gradients that are already resident in HBM.  The basis is fitted once before
+the timed region (gvq_fit_basis, reported separately: the paper refreshes it once per
+L_t + L_c iterations).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fit-gradients", type=int, default=None,
+                    help="override L (gradients the basis is fitted on)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (the N workers are simulated as N "
+                 "device buffers on it); --gpus above 1 is not supported.")
+
+    import numpy as np
+    import torch
+
+    from paper_1811_03617_amd import WORKLOADS, gvq, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = WORKLOADS[args.workload]
+    L = args.fit_gradients or w.L
+    es = 2 if w.dtype == "bf16" else 4
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    # ---- inputs, resident in HBM ------------------------------------------------------
+    basis = gvq.Basis(w.M, w.d, w.k, w.block_offsets(), w.dtype)
+    S = basis.S
+    workers = synth.worker_gradients(w, dev)
+    fit_grads = synth.fit_gradients(w, dev, L=L)
+    comps = [torch.empty(S * w.k, device=dev, dtype=torch.float32) for _ in range(w.N)]
+    total = torch.empty(S * w.k, device=dev, dtype=torch.float32)
+    out = torch.empty(w.M, device=dev, dtype=tdt)
+    torch.cuda.synchronize()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- basis refresh (timed on its own) -----------------------------------------------
+    basis.fit(fit_grads)
+    sweeps = basis.fit_status()
+    e0, e1 = ev(), ev()
+    e0.record()
+    basis.fit(fit_grads)
+    e1.record()
+    torch.cuda.synchronize()
+    fit_ms = e0.elapsed_time(e1)
+    del fit_grads
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        for g, c in zip(workers, comps):
+            basis.compress(g, w.N, c)
+        if events is not None:
+            events[1].record()
+        basis.aggregate(comps, total)
+        if events is not None:
+            events[2].record()
+        basis.decompress(total, out)
+        if events is not None:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(marks[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    comp_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps / w.N   # per launch
+    agg_ms = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
+    dec_ms = sum(m[2].elapsed_time(m[3]) for m in marks) / args.steps
+    dev_ms = marks[0][0].elapsed_time(marks[-1][3]) / args.steps
+
+    # ---- algorithmic traffic (bytes every kernel must move at least once) -----------------
+    comp_bytes = S * (w.d * es + 4 * w.k)                 # one compress launch
+    agg_bytes = (w.N + 1) * S * 4 * w.k
+    dec_bytes = S * (4 * w.k + w.d * es)
+    path_bytes = w.N * comp_bytes + agg_bytes + dec_bytes
+    grad_bytes = w.N * w.M * es
+
+    ms_per_step = max(wall_ms, dev_ms)
+    value = grad_bytes / ms_per_step / 1e6                # GB/s of gradient through the path
+    eff = path_bytes / ms_per_step / 1e6
+
+    # reconstruction quality (the paper's loss ||ghat - g||^2 / ||g||^2), as a sanity number
+    gsum = torch.zeros(w.M, device=dev, dtype=torch.float64)
+    for g in workers:
+        gsum += g.double()
+    loss = float(((out.double() - gsum) ** 2).sum() / (gsum ** 2).sum())
+    del gsum
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(w.name, {}).get("compress_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    res = {
+        "metric": "GB/s fp32 gradient through compress+aggregate+decompress; % of HBM peak",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: M={w.M} d={w.d} k={w.k} N={w.N} L={L} bases={w.n_blocks} "
+                               f"store={w.dtype}"},
+        "hbm_effective_GBs": round(eff, 1),
+        "pct_of_hbm_peak": round(100.0 * eff / HBM_PEAK_GBS, 2),
+        "path_algorithmic_bytes": path_bytes,
+        "kernels_ms": {"compress_per_launch": round(comp_ms, 4), "aggregate": round(agg_ms, 4),
+                       "decompress": round(dec_ms, 4)},
+        "kernels_GBs": {"compress": round(comp_bytes / comp_ms / 1e6, 1),
+                        "aggregate": round(agg_bytes / agg_ms / 1e6, 1),
+                        "decompress": round(dec_bytes / dec_ms / 1e6, 1)},
+        "fit": {"ms": round(fit_ms, 3), "L": L, "jacobi_sweeps": sweeps,
+                "input_GBs": round(L * w.M * es / fit_ms / 1e6, 1)},
+        "reconstruction_loss": loss,
+        "roofline": {"bound": "hbm", "kernel": "compress", "achieved": round(comp_bytes / comp_ms / 1e6, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(comp_bytes / comp_ms / 1e6 / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes_per_launch": comp_bytes, "traffic": traffic},
+    }
+
+    # ---- the float64 oracle on the host cores, same inputs, bounded sample --------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        U32, mu32, _ = basis.export()
+        U64, mu64 = U32.astype(np.float64), mu32.astype(np.float64)
+        offs = w.block_offsets()
+        threads = oracle.num_threads()
+
+        def run_oracle(ns):
+            """compress x N + aggregate + decompress on the first ns slices."""
+            hosts = [synth.to_numpy(g[: min(w.M, ns * w.d)]) for g in workers]
+            sub_offs = None
+            if offs is not None:
+                sub_offs = [o for o in offs if o < ns] + [ns]
+            Us, mus = (U64, mu64) if offs is None else (U64[: len(sub_offs) - 1], mu64[: len(sub_offs) - 1])
+            t = time.perf_counter()
+            ys = [oracle.compress(h, Us, mus, w.N, dtype=w.dtype, offsets=sub_offs) for h in hosts]
+            Y = oracle.aggregate(ys)
+            oracle.decompress(Y, Us, mus, hosts[0].shape[0], offsets=sub_offs)
+            return time.perf_counter() - t
+
+        probe = min(S, 1 << 13)
+        t_probe = run_oracle(probe)
+        ns = int(min(S, max(probe, probe * 15.0 / max(t_probe, 1e-6))))   # aim at ~15 s
+        t_cpu = run_oracle(ns)
+        sample_bytes = w.N * min(w.M, ns * w.d) * es
+        res["cpu_baseline"] = {"value": round(sample_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
+                               "cores": threads, "kind": "oracle",
+                               "sample": f"first {ns} of {S} slices of all {w.N} workers "
+                                         f"({sample_bytes / 1e9:.2f} GB of gradient), {t_cpu:.1f} s"}
+    basis.close()
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

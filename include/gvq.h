@@ -150,8 +150,11 @@ int gvq_basis_import(gvq_basis_t* h, const float* U, const float* mu);
 const char* gvq_strerror(int status);
 
 /*
- * Launch tuning (benchmarks only): option 0 = workgroups per compute unit for the
- * streaming kernels (0 restores the default).  Returns GVQ_EINVAL for unknown options.
+ * Launch tuning (benchmarks only), process-wide; value 0 restores the default.
+ *   option 0: workgroups per compute unit for the streaming kernels;
+ *   option 1: consecutive 16-slice tiles a wave takes before it jumps ahead by the width
+ *             of the whole grid (1 = interleave single tiles, large = one chunk per wave).
+ * Returns GVQ_EINVAL for unknown options or negative values.
  */
 int gvq_set_option(int option, int value);
 

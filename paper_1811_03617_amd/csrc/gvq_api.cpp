@@ -12,6 +12,7 @@
 static thread_local char g_hip_msg[256] = "no HIP error recorded";
 static thread_local char g_msg[320];
 static int g_wg_per_cu = 0;
+static int g_run_tiles = 0;
 
 int gvq_hip_fail(hipError_t e, const char* what)
 {
@@ -21,6 +22,7 @@ int gvq_hip_fail(hipError_t e, const char* what)
 }
 
 int gvq_opt_wg_per_cu() { return g_wg_per_cu; }
+int gvq_opt_run_tiles() { return g_run_tiles; }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -46,6 +48,7 @@ const char* gvq_strerror(int status)
 int gvq_set_option(int option, int value)
 {
     if (option == 0 && value >= 0 && value <= 64) { g_wg_per_cu = value; return GVQ_OK; }
+    if (option == 1 && value >= 0) { g_run_tiles = value; return GVQ_OK; }
     return GVQ_EINVAL;
 }
 
@@ -53,7 +56,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_U, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_mom, h->d_sweeps};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_mom, h->d_sweeps};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
@@ -106,6 +109,11 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_offs, sizeof(int64_t) * (B + 1)));
         TRY(hipMalloc((void**)&h->d_U, sizeof(float) * B * d * k));
         TRY(hipMalloc((void**)&h->d_mu, sizeof(float) * B * d));
+        if (gvq_mfma_shape(d, k)) {
+            const size_t kp = k <= 16 ? 16 : 32;
+            TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * d * kp));
+            TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * d * kp));
+        }
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
         TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
@@ -113,6 +121,20 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
         TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
         TRY(hipMemcpy(h->d_offs, h->h_offs, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
+        if (n_blocks > 1) {
+            const int64_t T = (S + 15) / 16;
+            int* tb = (int*)malloc(sizeof(int) * (size_t)T);
+            if (!tb) { rc = GVQ_ENOMEM; goto fail; }
+            int b = 0;
+            for (int64_t t = 0; t < T; ++t) {
+                while (h->h_offs[b + 1] <= t * 16) ++b;
+                tb[t] = b;
+            }
+            e = hipMalloc((void**)&h->d_tile_block, sizeof(int) * (size_t)T);
+            if (e == hipSuccess) e = hipMemcpy(h->d_tile_block, tb, sizeof(int) * (size_t)T, hipMemcpyHostToDevice);
+            free(tb);
+            if (e != hipSuccess) { rc = gvq_hip_fail(e, "tile_block upload"); goto fail; }
+        }
         TRY(hipMemset(h->d_eig, 0, sizeof(double) * B * d));
     }
 #undef TRY
@@ -239,6 +261,10 @@ int gvq_basis_import(gvq_basis_t* h, const float* U, const float* mu)
     GVQ_HIP(hipMemcpy(h->d_U, U, sizeof(float) * B * h->d * h->k, hipMemcpyHostToDevice));
     GVQ_HIP(hipMemcpy(h->d_mu, mu, sizeof(float) * B * h->d, hipMemcpyHostToDevice));
     GVQ_HIP(hipMemset(h->d_eig, 0, sizeof(double) * B * h->d));
+    {
+        int rc = gvq_launch_pack(h, nullptr);
+        if (rc != GVQ_OK) return rc;
+    }
     GVQ_HIP(hipDeviceSynchronize());
     h->fitted = true;
     h->has_cov = false;

@@ -19,16 +19,22 @@ typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 #define WAVES_PER_WG 4
 #define WG_THREADS (64 * WAVES_PER_WG)
 #define TILE_SLICES 16
+#ifndef GVQ_NONTEMPORAL
+#define GVQ_NONTEMPORAL 1  // gradients are touched once: keep them out of the way of the caches
+#endif
 
 struct CodecArgs {
     const void* in;       // compress: gradient; decompress: compressed [S][k]
     void* out;            // compress: compressed [S][k]; decompress: gradient
     const float* U;       // [B][d][k]
+    const f4* Upack;      // MFMA-operand order copy of U for this kernel, see pack_basis_kernel
     const float* mu;      // [B][d]
     const int64_t* offs;  // [B+1] slice offsets of the bases
     int64_t M, S;
     int B, d, k;
     float n_workers;      // compress only
+    const int* tile_block;  // [T] basis of the first slice of every 16-slice tile (B > 1 only)
+    int run_tiles;        // tile schedule, see TileIter
 };
 
 // Largest b with offs[b] <= j (offs[0] = 0, offs[B] = S > j).
@@ -55,16 +61,78 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Orders this wave's LDS traffic for the compiler: what one lane wrote is read by another
+// lane of the same wave afterwards.  The hardware executes a wave's LDS instructions in
+// order, so no s_barrier is needed; this only stops the compiler from moving LDS accesses
+// across the exchange point.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T>
+__device__ __forceinline__ T stream_load(const T* p)
+{
+#if GVQ_NONTEMPORAL
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void stream_store(T* p, T v)
+{
+#if GVQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Which tiles a wave works on: runs of R consecutive 16-slice tiles, run r = w, w+W, w+2W, ...
+// for wave w of W.  R = 1 interleaves single tiles, so that at any moment the whole chip
+// reads one compact window of memory (what HBM likes best); a longer run keeps a wave inside
+// one basis for longer when there are many bases; R = ceil(T/W) gives every wave one
+// contiguous chunk.
+struct TileIter {
+    int64_t t, run, run_end, T, W;
+    int R;
+    __device__ __forceinline__ bool init(int64_t T_, int R_)
+    {
+        T = T_; R = R_;
+        W = (int64_t)gridDim.x * WAVES_PER_WG;
+        run = (int64_t)blockIdx.x * WAVES_PER_WG + (threadIdx.x >> 6);
+        t = run * R;
+        run_end = t + R < T ? t + R : T;
+        return t < T;
+    }
+    __device__ __forceinline__ bool advance()
+    {
+        if (++t < run_end) return true;
+        run += W;
+        t = run * R;
+        run_end = t + R < T ? t + R : T;
+        return t < T;
+    }
+};
+
+__device__ __forceinline__ int block_of_tile(const CodecArgs& a, int64_t t)
+{
+    return a.B > 1 ? a.tile_block[t] : 0;
+}
+
 // --------------------------------------------------------------------------------------
 // compress, MFMA path.  D in {16,32,64,128}, NT = ceil(k/16) in {1,2}.
 //
-// One wave owns a contiguous range of 16-slice tiles.  Per tile: every lane loads 128-bit
-// words of the tile in memory order (fully coalesced: the tile is one contiguous run of
-// 16*D elements), subtracts mu/N, and parks them in the wave's private LDS region; the
-// lanes then read the same data back in the B-operand order (lane = slice, 4 consecutive
-// elements per 128-bit read).  Chunk c (4 floats) of slice s lives at 128-bit slot
-// s*CPS + (c ^ swz(s)), a XOR swizzle that keeps 8 consecutive lanes on 8 distinct
-// 128-bit bank groups for the transposed read.
+// Per 16-slice tile a wave loads 128-bit words in memory order (fully coalesced: the tile
+// is one contiguous run of 16*D elements), subtracts mu/N, and parks them in its private
+// LDS region; the lanes then read the data back in the B-operand order (lane = slice, 4
+// consecutive elements per 128-bit read).  Chunk c (4 floats) of slice s lives at 128-bit
+// slot s*CPS + (c ^ swz(s)), a XOR swizzle that keeps 8 consecutive lanes on 8 distinct
+// 128-bit bank groups for the transposed read.  The loads of the next tile are in flight
+// while the current one is multiplied.
 // The contraction index may be visited in any order as long as U follows: MFMA step
 // (q, j) multiplies elements e = 4*(4q + kk) + j, kk = l/16.
 // --------------------------------------------------------------------------------------
@@ -75,7 +143,7 @@ __device__ __forceinline__ int swz(int s)
 }
 
 template <int D, int NT, bool BF16>
-__global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
+__global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs a)
 {
     constexpr int CPS = D / 4;                    // fp32 128-bit chunks per slice
     constexpr int EPL = BF16 ? 8 : 4;             // elements per 128-bit global load
@@ -83,40 +151,33 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
     constexpr int TILE_LOADS = TILE_SLICES * LCPS;  // 128-bit loads per tile
     constexpr int NL = (TILE_LOADS + 63) / 64;    // loads per lane per tile
     constexpr int NQ = CPS / 4;                   // 128-bit LDS reads per lane per tile
+    constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
 
     __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    f4* lds = lds_all[wave];
+    f4* lds = lds_all[threadIdx.x >> 6];
 
     const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
-    const int64_t W = (int64_t)gridDim.x * WAVES_PER_WG;
-    const int64_t w = (int64_t)blockIdx.x * WAVES_PER_WG + wave;
-    const int64_t t0 = w * T / W, t1 = (w + 1) * T / W;
-    if (t0 >= t1) return;
+    TileIter it;
+    if (!it.init(T, a.run_tiles)) return;
 
     const int n_ = lane & 15, kk = lane >> 4;
-    // this lane's fixed position inside every tile, for the coalesced loads
-    const int lc = lane % LCPS;                   // load chunk within the slice
+    const int lc = lane % LCPS;                   // this lane's load chunk within a slice
+    const bool loads = lane < TILE_LOADS;         // false only for the upper lanes at D = 16, bf16
 
     // ---- per-basis state -------------------------------------------------------------
-    int cur_b = find_block(a.offs, a.B, t0 * TILE_SLICES);
+    int cur_b = block_of_tile(a, it.t);
     int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
-    float ufrag[NQ][4][NT];
+    f4 uf[NQ][NT];   // uf[q][nt][j] = U[4*(4q + kk) + j][16nt + n_], zero past column k
     float mun[EPL];
 
     auto load_basis = [&](int b) {
-        const float* Ub = a.U + (size_t)b * D * a.k;
+        const f4* Up = a.Upack + (size_t)b * (NQ * NT * 64) + lane;
         const float* mub = a.mu + (size_t)b * D;
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    int e = 4 * (4 * q + kk) + j, c = 16 * nt + n_;
-                    ufrag[q][j][nt] = c < a.k ? Ub[e * a.k + c] : 0.0f;
-                }
+            for (int nt = 0; nt < NT; ++nt) uf[q][nt] = Up[(q * NT + nt) * 64];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) mun[i] = mub[lc * EPL + i] / a.n_workers;
     };
@@ -125,28 +186,34 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
     // ---- tile loads --------------------------------------------------------------------
     u4 regs[NL];
     auto load_tile = [&](int64_t t) {
-        const int64_t base = t * TILE_SLICES * (int64_t)D;  // first element of the tile
+        const int64_t base = t * TILE_ELEMS;  // first element of the tile
+        if (base + TILE_ELEMS <= a.M) {       // interior tile: no bounds checks
+#pragma unroll
+            for (int r = 0; r < NL; ++r) {
+                const int g = r * 64 + lane;
+                if (NL * 64 == TILE_LOADS || loads)
+                    regs[r] = stream_load((const u4*)((const char*)a.in + (base + (int64_t)g * EPL) * (BF16 ? 2 : 4)));
+            }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < NL; ++r) {
-            int g = r * 64 + lane;
+            const int g = r * 64 + lane;
             u4 v = {0u, 0u, 0u, 0u};
-            if (g < TILE_LOADS) {
-                int64_t e0 = base + (int64_t)g * EPL;
+            const int64_t e0 = base + (int64_t)g * EPL;
+            if (g < TILE_LOADS && e0 < a.M) {
                 if (e0 + EPL <= a.M) {
                     v = *(const u4*)((const char*)a.in + e0 * (BF16 ? 2 : 4));
-                } else if (e0 < a.M) {
-                    if (BF16) {
-                        const unsigned short* p = (const unsigned short*)a.in;
-                        unsigned int h[8];
+                } else if (BF16) {
+                    const unsigned short* p = (const unsigned short*)a.in;
+                    unsigned int h[8];
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) h[i] = e0 + i < a.M ? p[e0 + i] : 0u;
-                        v = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                               h[6] | (h[7] << 16)};
-                    } else {
-                        const unsigned int* p = (const unsigned int*)a.in;
-                        v = u4{p[e0], e0 + 1 < a.M ? p[e0 + 1] : 0u, e0 + 2 < a.M ? p[e0 + 2] : 0u,
-                               e0 + 3 < a.M ? p[e0 + 3] : 0u};
-                    }
+                    for (int i = 0; i < 8; ++i) h[i] = e0 + i < a.M ? p[e0 + i] : 0u;
+                    v = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                } else {
+                    const unsigned int* p = (const unsigned int*)a.in;
+                    v = u4{p[e0], e0 + 1 < a.M ? p[e0 + 1] : 0u, e0 + 2 < a.M ? p[e0 + 2] : 0u,
+                           e0 + 3 < a.M ? p[e0 + 3] : 0u};
                 }
             }
             regs[r] = v;
@@ -156,10 +223,10 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
     auto stage_tile = [&]() {
 #pragma unroll
         for (int r = 0; r < NL; ++r) {
-            int g = r * 64 + lane;
-            if (g < TILE_LOADS) {
-                int s = g / LCPS;
-                u4 v = regs[r];
+            const int g = r * 64 + lane;
+            if (NL * 64 == TILE_LOADS || loads) {
+                const int s = g / LCPS;
+                const u4 v = regs[r];
                 if (BF16) {
                     f4 lo = {bf16_to_f32(v.x & 0xffffu) - mun[0], bf16_to_f32(v.x >> 16) - mun[1],
                              bf16_to_f32(v.y & 0xffffu) - mun[2], bf16_to_f32(v.y >> 16) - mun[3]};
@@ -176,49 +243,52 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
         }
     };
 
-    load_tile(t0);
-    for (int64_t t = t0; t < t1; ++t) {
+    load_tile(it.t);
+    for (bool more = true; more;) {
+        const int64_t t = it.t;
         const int64_t s0 = t * TILE_SLICES;
         const int64_t s1 = s0 + TILE_SLICES < a.S ? s0 + TILE_SLICES : a.S;
-        if (s0 >= blk_end) {  // the previous tile ended exactly on a basis boundary, or bases were skipped
-            cur_b = find_block(a.offs, a.B, s0);
+        if (s0 >= blk_end || s0 < blk_begin) {  // this tile starts in another basis
+            cur_b = block_of_tile(a, t);
             blk_begin = a.offs[cur_b];
             blk_end = a.offs[cur_b + 1];
             load_basis(cur_b);
         }
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_sync();
         stage_tile();
-        __builtin_amdgcn_wave_barrier();
-        if (t + 1 < t1) load_tile(t + 1);
+        wave_lds_sync();
+        more = it.advance();
+        if (more) load_tile(it.t);
 
         for (;;) {
+            f4 x[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) x[q] = lds[n_ * CPS + ((4 * q + kk) ^ swz<D>(n_))];
             f4 acc[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                f4 x = lds[n_ * CPS + ((4 * q + kk) ^ swz<D>(n_))];
+            for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(ufrag[q][j][nt], x[j], acc[nt], 0, 0, 0);
-            }
+                        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[q][j], acc[nt], 0, 0, 0);
             // lane holds comps 16*nt + 4*kk + r of slice s0 + n_
             const int64_t j = s0 + n_;
             const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
             if (j >= lo && j < hi) {
                 float* o = (float*)a.out + j * a.k;
+                if ((a.k & 3) == 0) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    int c0 = 16 * nt + 4 * kk;
-                    if ((a.k & 3) == 0) {
-                        if (c0 < a.k) *(f4*)(o + c0) = acc[nt];
-                    } else {
+                    for (int nt = 0; nt < NT; ++nt)
+                        if (16 * nt + 4 * kk < a.k) stream_store((f4*)(o + 16 * nt + 4 * kk), acc[nt]);
+                } else {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            if (c0 + r < a.k) o[c0 + r] = acc[nt][r];
-                    }
+                            if (16 * nt + 4 * kk + r < a.k) o[16 * nt + 4 * kk + r] = acc[nt][r];
                 }
             }
             if (blk_end >= s1) break;
@@ -230,12 +300,11 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
             blk_begin = blk_end;
             blk_end = a.offs[cur_b + 1];
             load_basis(cur_b);
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_sync();
+            if (loads) {
 #pragma unroll
-            for (int r = 0; r < NL; ++r) {
-                int g = r * 64 + lane;
-                if (g < TILE_LOADS) {
-                    int s = g / LCPS;
+                for (int r = 0; r < NL; ++r) {
+                    const int s = (r * 64 + lane) / LCPS;
                     if (BF16) {
                         f4* p0 = &lds[s * CPS + ((2 * lc) ^ swz<D>(s))];
                         f4* p1 = &lds[s * CPS + ((2 * lc + 1) ^ swz<D>(s))];
@@ -256,7 +325,7 @@ __global__ __launch_bounds__(WG_THREADS) void compress_mfma_kernel(CodecArgs a)
                     }
                 }
             }
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_sync();
         }
     }
 }
@@ -290,40 +359,42 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
 // A = U tile (16 elements x 4 comps), B = Y (4 comps x 16 slices): lane (n = l%16, kk = l/16)
 // loads comps 16q + 4kk + {0..3} of slice n as one 128-bit word and MFMA step (q, j)
 // contracts comp 16q + 4kk + j.  Result register r of element tile et is element
-// 16et + 4kk + r of slice n, so each lane stores 4 consecutive outputs per tile.
+// 16et + 4kk + r of slice n.  The 16 x D result tile is one contiguous run of memory, so
+// it goes through the wave's LDS region (same swizzle as compress) and leaves as
+// full-width 128-bit stores in memory order.
 // --------------------------------------------------------------------------------------
 template <int D, int NQ, bool OUT_BF16>
-__global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a)
+__global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArgs a)
 {
     constexpr int ET = D / 16;
+    constexpr int CPS = D / 4;                       // fp32 128-bit chunks per slice
+    constexpr int EPS = OUT_BF16 ? 8 : 4;            // elements per 128-bit store
+    constexpr int SCPS = D / EPS;                    // store chunks per slice
+    constexpr int TILE_STORES = TILE_SLICES * SCPS;
+    constexpr int NS = (TILE_STORES + 63) / 64;      // stores per lane per tile
+    constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
+
+    __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    f4* lds = lds_all[threadIdx.x >> 6];
     const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
-    const int64_t W = (int64_t)gridDim.x * WAVES_PER_WG;
-    const int64_t w = (int64_t)blockIdx.x * WAVES_PER_WG + wave;
-    const int64_t t0 = w * T / W, t1 = (w + 1) * T / W;
-    if (t0 >= t1) return;
+    TileIter it;
+    if (!it.init(T, a.run_tiles)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const float* Y = (const float*)a.in;
 
-    int cur_b = find_block(a.offs, a.B, t0 * TILE_SLICES);
+    int cur_b = block_of_tile(a, it.t);
     int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
-    float ufrag[ET][NQ][4];
+    f4 uf[ET][NQ];   // uf[et][q][j] = U[16et + n_][16q + 4kk + j], zero past column k
     f4 mu4[ET];
     auto load_basis = [&](int b) {
-        const float* Ub = a.U + (size_t)b * D * a.k;
-        const float* mub = a.mu + (size_t)b * D;
+        const f4* Up = a.Upack + (size_t)b * (ET * NQ * 64) + lane;
+        const f4* mub = (const f4*)(a.mu + (size_t)b * D) + kk;
 #pragma unroll
         for (int et = 0; et < ET; ++et) {
 #pragma unroll
-            for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    int c = 16 * q + 4 * kk + j;
-                    ufrag[et][q][j] = c < a.k ? Ub[(16 * et + n_) * a.k + c] : 0.0f;
-                }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mu4[et][r] = mub[16 * et + 4 * kk + r];
+            for (int q = 0; q < NQ; ++q) uf[et][q] = Up[(et * NQ + q) * 64];
+            mu4[et] = mub[4 * et];
         }
     };
     load_basis(cur_b);
@@ -331,14 +402,15 @@ __global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a
     f4 y[NQ];
     auto load_tile = [&](int64_t t) {
         const int64_t j = t * TILE_SLICES + n_;
+        const bool vec = (a.k & 3) == 0;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int c0 = 16 * q + 4 * kk;
             f4 v = {0.f, 0.f, 0.f, 0.f};
             if (j < a.S) {
                 const float* p = Y + j * a.k + c0;
-                if ((a.k & 3) == 0) {
-                    if (c0 < a.k) v = *(const f4*)p;
+                if (vec) {
+                    if (c0 < a.k) v = stream_load((const f4*)p);
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
@@ -349,12 +421,13 @@ __global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a
         }
     };
 
-    load_tile(t0);
-    for (int64_t t = t0; t < t1; ++t) {
+    load_tile(it.t);
+    for (bool more = true; more;) {
+        const int64_t t = it.t;
         const int64_t s0 = t * TILE_SLICES;
         const int64_t s1 = s0 + TILE_SLICES < a.S ? s0 + TILE_SLICES : a.S;
-        if (s0 >= blk_end) {
-            cur_b = find_block(a.offs, a.B, s0);
+        if (s0 >= blk_end || s0 < blk_begin) {
+            cur_b = block_of_tile(a, t);
             blk_begin = a.offs[cur_b];
             blk_end = a.offs[cur_b + 1];
             load_basis(cur_b);
@@ -362,12 +435,11 @@ __global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a
         f4 yc[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q) yc[q] = y[q];
-        if (t + 1 < t1) load_tile(t + 1);
+        more = it.advance();
+        if (more) load_tile(it.t);
 
         for (;;) {
-            const int64_t j = s0 + n_;
-            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
-            const bool mine = j >= lo && j < hi;
+            wave_lds_sync();
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
                 f4 acc = mu4[et];
@@ -375,29 +447,45 @@ __global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ufrag[et][q][jj], yc[q][jj], acc, 0, 0, 0);
-                if (mine) {
-                    const int64_t e0 = j * D + 16 * et + 4 * kk;
-                    if (OUT_BF16) {
-                        unsigned short* o = (unsigned short*)a.out;
-                        if (e0 + 4 <= a.M) {
-                            u2 pk = {f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16),
-                                     f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16)};
-                            *(u2*)(o + e0) = pk;
-                        } else {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[et][q][jj], yc[q][jj], acc, 0, 0, 0);
+                lds[n_ * CPS + ((4 * et + kk) ^ swz<D>(n_))] = acc;
+            }
+            wave_lds_sync();
+            // write the tile out in memory order
+            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
+            const bool whole = lo == s0 && hi == s0 + TILE_SLICES && (s0 + TILE_SLICES) * (int64_t)D <= a.M;
 #pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                if (e0 + r < a.M) o[e0 + r] = (unsigned short)f32_to_bf16_rne(acc[r]);
-                        }
-                    } else {
-                        float* o = (float*)a.out;
-                        if (e0 + 4 <= a.M) {
-                            *(f4*)(o + e0) = acc;
-                        } else {
+            for (int r = 0; r < NS; ++r) {
+                const int g = r * 64 + lane;
+                if (NS * 64 != TILE_STORES && g >= TILE_STORES) continue;
+                const int s = g / SCPS, c = g % SCPS;
+                const int64_t e0 = s0 * D + (int64_t)g * EPS;
+                if (OUT_BF16) {
+                    const f4 v0 = lds[s * CPS + ((2 * c) ^ swz<D>(s))];
+                    const f4 v1 = lds[s * CPS + ((2 * c + 1) ^ swz<D>(s))];
+                    unsigned short* o = (unsigned short*)a.out;
+                    if (whole || (s0 + s >= lo && s0 + s < hi && e0 + 8 <= a.M)) {
+                        u4 pk = {f32_to_bf16_rne(v0[0]) | (f32_to_bf16_rne(v0[1]) << 16),
+                                 f32_to_bf16_rne(v0[2]) | (f32_to_bf16_rne(v0[3]) << 16),
+                                 f32_to_bf16_rne(v1[0]) | (f32_to_bf16_rne(v1[1]) << 16),
+                                 f32_to_bf16_rne(v1[2]) | (f32_to_bf16_rne(v1[3]) << 16)};
+                        stream_store((u4*)(o + e0), pk);
+                    } else if (s0 + s >= lo && s0 + s < hi) {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                if (e0 + r < a.M) o[e0 + r] = acc[r];
+                        for (int i = 0; i < 4; ++i) {
+                            if (e0 + i < a.M) o[e0 + i] = (unsigned short)f32_to_bf16_rne(v0[i]);
+                            if (e0 + 4 + i < a.M) o[e0 + 4 + i] = (unsigned short)f32_to_bf16_rne(v1[i]);
                         }
+                    }
+                } else {
+                    const f4 v = lds[s * CPS + (c ^ swz<D>(s))];
+                    float* o = (float*)a.out;
+                    if (whole || (s0 + s >= lo && s0 + s < hi && e0 + 4 <= a.M)) {
+                        stream_store((f4*)(o + e0), v);
+                    } else if (s0 + s >= lo && s0 + s < hi) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (e0 + i < a.M) o[e0 + i] = v[i];
                     }
                 }
             }
@@ -408,6 +496,7 @@ __global__ __launch_bounds__(WG_THREADS) void decompress_mfma_kernel(CodecArgs a
             load_basis(cur_b);
         }
     }
+    (void)TILE_ELEMS;
 }
 
 // decompress, any d, k: one thread per output element.
@@ -432,35 +521,87 @@ __global__ __launch_bounds__(256) void decompress_generic_kernel(CodecArgs a)
 }
 
 // --------------------------------------------------------------------------------------
-// aggregate: out[i] = ((in0[i] + in1[i]) + in2[i]) + ...   128 bits per lane per input.
+// aggregate: out[i] = ((in0[i] + in1[i]) + in2[i]) + ...   128 bits per lane per input, all
+// NIN loads of an element issued before the first add.
 // --------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void aggregate_kernel(gvq_ptrs in, int n, float* out, int64_t len)
+#define AGG_MAX_IN 16
+template <int NIN>
+__global__ __launch_bounds__(256) void aggregate_kernel(gvq_ptrs in, float* out, int64_t len)
 {
     const int64_t len4 = len >> 2;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < len4; i += stride) {
-        f4 acc = ((const f4*)in.p[0])[i];
-        for (int w = 1; w < n; ++w) acc += ((const f4*)in.p[w])[i];
-        ((f4*)out)[i] = acc;
+        f4 v[NIN];
+#pragma unroll
+        for (int w = 0; w < NIN; ++w) v[w] = stream_load((const f4*)in.p[w] + i);
+        f4 acc = v[0];
+#pragma unroll
+        for (int w = 1; w < NIN; ++w) acc += v[w];
+        stream_store((f4*)out + i, acc);
     }
     // up to 3 trailing numbers
-    const int64_t i = (len4 << 2) + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = (len4 << 2) + threadIdx.x;
     if (blockIdx.x == 0 && i < len) {
         float acc = ((const float*)in.p[0])[i];
-        for (int w = 1; w < n; ++w) acc += ((const float*)in.p[w])[i];
+#pragma unroll
+        for (int w = 1; w < NIN; ++w) acc += ((const float*)in.p[w])[i];
         out[i] = acc;
+    }
+}
+
+// --------------------------------------------------------------------------------------
+// Copies of U in the order the MFMA kernels consume it, so that a wave fetches its operand
+// registers with contiguous 128-bit loads (both are d x KP floats per basis, KP = k rounded
+// up to 16, zero past column k):
+//   compress:   Upc[b][q][nt][lane][j] = U[4*(4q + kk) + j][16nt + n],  n = lane%16, kk = lane/16
+//   decompress: Upd[b][et][q][lane][j] = U[16et + n][16q + 4kk + j]
+// --------------------------------------------------------------------------------------
+__global__ void pack_basis_kernel(const float* U, float* Upc, float* Upd, int d, int k, int NT)
+{
+    const int b = blockIdx.x;
+    const float* Ub = U + (size_t)b * d * k;
+    const int per = d * 16 * NT;  // floats per basis in either packed copy
+    const int NQc = d / 16, ET = d / 16;
+    for (int i = threadIdx.x; i < per; i += blockDim.x) {
+        const int j = i & 3, lane = (i >> 2) & 63, n = lane & 15, kk = lane >> 4, hi = i >> 8;
+        {   // compress order: hi = q*NT + nt
+            const int q = hi / NT, nt = hi % NT;
+            const int e = 4 * (4 * q + kk) + j, c = 16 * nt + n;
+            Upc[(size_t)b * per + i] = (q < NQc && c < k) ? Ub[e * k + c] : 0.0f;
+        }
+        {   // decompress order: hi = et*NT + q
+            const int et = hi / NT, q = hi % NT;
+            const int e = 16 * et + n, c = 16 * q + 4 * kk + j;
+            Upd[(size_t)b * per + i] = (et < ET && c < k) ? Ub[e * k + c] : 0.0f;
+        }
     }
 }
 
 // ======================================================================================
 // host side
 // ======================================================================================
-static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_workers)
+bool gvq_mfma_shape(int d, int k)
+{
+    return k <= 32 && (d == 16 || d == 32 || d == 64 || d == 128);
+}
+
+int gvq_launch_pack(const gvq_basis* h, hipStream_t st)
+{
+    if (!gvq_mfma_shape(h->d, h->k)) return GVQ_OK;
+    hipLaunchKernelGGL(pack_basis_kernel, dim3(h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd,
+                       h->d, h->k, h->k <= 16 ? 1 : 2);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_workers, const float* upack)
 {
     CodecArgs a;
-    a.in = in; a.out = out; a.U = h->d_U; a.mu = h->d_mu; a.offs = h->d_offs;
+    a.in = in; a.out = out; a.U = h->d_U; a.Upack = (const f4*)upack; a.mu = h->d_mu; a.offs = h->d_offs;
     a.M = h->M; a.S = h->S; a.B = h->B; a.d = h->d; a.k = h->k;
     a.n_workers = (float)n_workers;
+    a.tile_block = h->d_tile_block;
+    a.run_tiles = 1;
     return a;
 }
 
@@ -480,13 +621,27 @@ static int streaming_grid(const gvq_basis* h, K kernel, int64_t tiles)
     return (int)(g < 1 ? 1 : g);
 }
 
+// Tiles per run for the MFMA kernels (see TileIter): the tuning option if set, else single
+// tiles for one basis and short runs when there are many bases.
+static int run_length(const gvq_basis* h, int64_t tiles, int grid)
+{
+    const int64_t waves = (int64_t)grid * WAVES_PER_WG;
+    const int64_t chunk = (tiles + waves - 1) / waves;   // run length that gives one run per wave
+    int64_t r = gvq_opt_run_tiles();
+    if (r <= 0) r = h->B > 1 ? 4 : 1;
+    if (r > chunk) r = chunk;
+    return (int)(r < 1 ? 1 : r);
+}
+
 template <int D, int NT, bool BF16>
 static int launch_compress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     auto kern = compress_mfma_kernel<D, NT, BF16>;
     int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, a);
+    CodecArgs b = a;
+    b.run_tiles = run_length(h, tiles, grid);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
@@ -499,9 +654,9 @@ static int launch_compress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t
 
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out, hipStream_t st)
 {
-    CodecArgs a = make_args(h, grad, out, n_workers);
+    CodecArgs a = make_args(h, grad, out, n_workers, h->d_Upc);
     const bool bf = h->dtype == GVQ_BF16;
-    if (h->k <= 32) {
+    if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
         case 16: return bf ? launch_compress_d<16, true>(h, a, st) : launch_compress_d<16, false>(h, a, st);
         case 32: return bf ? launch_compress_d<32, true>(h, a, st) : launch_compress_d<32, false>(h, a, st);
@@ -527,7 +682,9 @@ static int launch_decompress_t(const gvq_basis* h, const CodecArgs& a, hipStream
     auto kern = decompress_mfma_kernel<D, NQ, OBF>;
     int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, a);
+    CodecArgs b = a;
+    b.run_tiles = run_length(h, tiles, grid);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
@@ -540,9 +697,9 @@ static int launch_decompress_d(const gvq_basis* h, const CodecArgs& a, hipStream
 
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt, hipStream_t st)
 {
-    CodecArgs a = make_args(h, comp, out, 1);
+    CodecArgs a = make_args(h, comp, out, 1, h->d_Upd);
     const bool bf = odt == GVQ_BF16;
-    if (h->k <= 32) {
+    if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
         case 16: return bf ? launch_decompress_d<16, true>(h, a, st) : launch_decompress_d<16, false>(h, a, st);
         case 32: return bf ? launch_decompress_d<32, true>(h, a, st) : launch_decompress_d<32, false>(h, a, st);
@@ -561,20 +718,31 @@ int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_
     return GVQ_OK;
 }
 
+template <int NIN>
+static void launch_aggregate_n(int n, int grid, hipStream_t st, const gvq_ptrs& p, float* out, int64_t len)
+{
+    if constexpr (NIN > 1) {
+        if (n < NIN) { launch_aggregate_n<NIN - 1>(n, grid, st, p, out, len); return; }
+    }
+    hipLaunchKernelGGL(aggregate_kernel<NIN>, dim3(grid), dim3(256), 0, st, p, out, len);
+}
+
 int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, float* out, hipStream_t st)
 {
     const int64_t len = h->S * h->k;
-    int64_t want = ((len >> 2) + 255) / 256, cap = (int64_t)h->num_cu * 8;
+    int per_cu = gvq_opt_wg_per_cu();
+    if (per_cu <= 0) per_cu = 2;
+    int64_t want = ((len >> 2) + 255) / 256, cap = (int64_t)h->num_cu * per_cu;
     int grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
-    // out = comps[0] + ... in groups of at most GVQ_MAX_PTRS; later groups start from out
+    // out = comps[0] + ... in groups of at most AGG_MAX_IN; later groups start from out
     int done = 0;
     while (done < N) {
         gvq_ptrs p;
         int n = 0;
         if (done > 0) p.p[n++] = out;
-        while (n < GVQ_MAX_PTRS && done < N) p.p[n++] = comps[done++];
-        hipLaunchKernelGGL(aggregate_kernel, dim3(grid), dim3(256), 0, st, p, n, out, len);
+        while (n < AGG_MAX_IN && done < N) p.p[n++] = comps[done++];
+        launch_aggregate_n<AGG_MAX_IN>(n, grid, st, p, out, len);
         GVQ_HIP(hipGetLastError());
     }
     return GVQ_OK;

@@ -329,5 +329,5 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st
     const int threads = d > 64 ? 1024 : (d > 16 ? 256 : 64);
     hipLaunchKernelGGL(eigen_kernel, dim3(h->B), dim3(threads), lds, st, e);
     GVQ_HIP(hipGetLastError());
-    return GVQ_OK;
+    return gvq_launch_pack(h, st);
 }

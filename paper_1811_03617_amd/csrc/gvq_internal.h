@@ -15,8 +15,11 @@ struct gvq_basis {
     int num_cu = 0;
     int64_t* h_offs = nullptr;  // host [B+1]
     int64_t* d_offs = nullptr;  // device [B+1]
+    int* d_tile_block = nullptr;  // device [ceil(S/16)]: basis of the first slice of each 16-slice tile (B > 1)
     float* d_U = nullptr;       // [B][d][k]
     float* d_mu = nullptr;      // [B][d]
+    float* d_Upc = nullptr;     // [B][d][KP] U in compress-MFMA operand order (MFMA shapes only)
+    float* d_Upd = nullptr;     // [B][d][KP] U in decompress-MFMA operand order
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
     double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
@@ -44,6 +47,8 @@ int gvq_hip_fail(hipError_t e, const char* what);
 
 // Workgroups per compute unit for the streaming kernels (0 = pick from occupancy).
 int gvq_opt_wg_per_cu();
+// Tiles per run in the MFMA kernels' schedule (0 = default).
+int gvq_opt_run_tiles();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out,
@@ -53,3 +58,6 @@ int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, f
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt,
                           hipStream_t st);
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
+// Refresh the operand-order copies of U after d_U changed (no-op for non-MFMA shapes).
+int gvq_launch_pack(const gvq_basis* h, hipStream_t st);
+bool gvq_mfma_shape(int d, int k);

@@ -30,6 +30,9 @@ def lib():
     the library cannot be built or loaded: there is no other code path."""
     global _lib
     if _lib is None:
+        # PyTorch owns the device memory this library works on, so both must talk to the same
+        # HIP runtime: load torch (and with it its libamdhip64) before libgvq resolves its own.
+        import torch  # noqa: F401
         if not os.path.exists(_build.LIB):
             _build.build()
         L = C.CDLL(_build.LIB)
