@@ -1,0 +1,223 @@
+"""Parity at the full sizes of the five benchmark workloads, in the launch configuration
+bench.py times (library defaults).  The float64 oracle checks sampled slice ranges one by
+one (it would need minutes for everything); a float64 PyTorch re-computation on the GPU
+covers every element of one worker's compressed vector and of the reconstructed gradient.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1811_03617_amd import WORKLOADS, gvq, synth
+from _util import ANGLE_TOL, REL_TOL, assert_close, bf16_bits_to_f64, max_angle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+NAMES = ["tiny", "resnet50", "alexnet", "vgg16", "vgg16_bf16"]
+
+
+def _sample_blocks(w):
+    B = w.n_blocks
+    return sorted(set([0, B - 1] + ([1, B // 2, B - 2] if B > 4 else list(range(B)))))
+
+
+def _oracle_basis_on_blocks(w, fit_np, blocks, rng):
+    """Oracle fit on the chosen basis blocks; the others get a random orthonormal basis."""
+    offs = w.block_offsets() or [0, w.S]
+    U = np.stack([np.linalg.qr(rng.standard_normal((w.d, w.k)))[0] for _ in range(w.n_blocks)])
+    mu = 0.01 * rng.standard_normal((w.n_blocks, w.d))
+    eig = np.zeros((w.n_blocks, w.d))
+    for b in blocks:
+        lo, hi = offs[b] * w.d, min(offs[b + 1] * w.d, w.M)
+        Ub, mub, eigb = oracle.fit([g[lo:hi] for g in fit_np], w.d, w.k, dtype=w.dtype)
+        U[b], mu[b], eig[b] = Ub[0], mub[0], eigb[0]
+    return U, mu, eig
+
+
+def _ranges(w, blocks, rng):
+    """Slice ranges to check with the oracle: both ends (ragged tail included), basis
+    boundaries, and random places; each spans several 16-slice tiles, unaligned."""
+    offs = w.block_offsets() or [0, w.S]
+    out = [(0, min(w.S, 300)), (max(0, w.S - 301), w.S)]
+    for b in blocks:
+        lo, hi = offs[b], offs[b + 1]
+        out.append((lo, min(hi, lo + 70)))
+        out.append((max(lo, hi - 70), hi))
+        if hi - lo > 400:
+            s = int(rng.integers(lo + 71, hi - 300))
+            out.append((s, s + 217))
+    return sorted(set(out))
+
+
+def _in_blocks(w, blocks, j0, j1):
+    offs = w.block_offsets() or [0, w.S]
+    ok = np.zeros(j1 - j0, dtype=bool)
+    for b in blocks:
+        lo, hi = max(offs[b], j0), min(offs[b + 1], j1)
+        if hi > lo:
+            ok[lo - j0:hi - j0] = True
+    return ok
+
+
+def _torch_reference(w, U64, mu64, x_dev, n_workers):
+    """float64 PyTorch: y = (x - mu/N) U per slice, with the per-slice basis gathered."""
+    S, d, k = w.S, w.d, w.k
+    offs = torch.tensor(w.block_offsets() or [0, S], device=DEV)
+    Ut = torch.from_numpy(U64).to(DEV)
+    mut = torch.from_numpy(mu64).to(DEV)
+    xp = torch.zeros(S * d, dtype=torch.float64, device=DEV)
+    xp[: w.M] = x_dev.double()
+    xp = xp.view(S, d)
+    y = torch.empty(S, k, dtype=torch.float64, device=DEV)
+    step = 1 << 15
+    for s0 in range(0, S, step):
+        s1 = min(S, s0 + step)
+        blk = torch.searchsorted(offs, torch.arange(s0, s1, device=DEV), right=True) - 1
+        if w.n_blocks == 1:
+            y[s0:s1] = (xp[s0:s1] - mut[0] / n_workers) @ Ut[0]
+        else:
+            y[s0:s1] = torch.einsum("nd,ndk->nk", xp[s0:s1] - mut[blk] / n_workers, Ut[blk])
+    return y
+
+
+def _torch_decompress(w, U64, mu64, Y):
+    S, d = w.S, w.d
+    offs = torch.tensor(w.block_offsets() or [0, S], device=DEV)
+    Ut = torch.from_numpy(U64).to(DEV)
+    mut = torch.from_numpy(mu64).to(DEV)
+    out = torch.empty(S, d, dtype=torch.float64, device=DEV)
+    step = 1 << 15
+    for s0 in range(0, S, step):
+        s1 = min(S, s0 + step)
+        blk = torch.searchsorted(offs, torch.arange(s0, s1, device=DEV), right=True) - 1
+        if w.n_blocks == 1:
+            out[s0:s1] = Y[s0:s1] @ Ut[0].T + mut[0]
+        else:
+            out[s0:s1] = torch.einsum("nk,ndk->nd", Y[s0:s1], Ut[blk]) + mut[blk]
+    return out.view(-1)[: w.M]
+
+
+def _rel(a, b):
+    return float((a - b).norm() / b.norm())
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_fullsize_codec(name):
+    w = WORKLOADS[name]
+    rng = np.random.default_rng(w.seed)
+    blocks = _sample_blocks(w)
+    fit_np = [synth.to_numpy(g) for g in synth.fit_gradients(w, DEV, L=2)]
+    U, mu, _ = _oracle_basis_on_blocks(w, fit_np, blocks, rng)
+    del fit_np
+    U32, mu32 = U.astype(np.float32), mu.astype(np.float32)
+    U64, mu64 = U32.astype(np.float64), mu32.astype(np.float64)
+
+    workers = synth.worker_gradients(w, DEV)
+    b = gvq.Basis(w.M, w.d, w.k, w.block_offsets(), w.dtype)
+    b.import_(U32, mu32)
+    comps = [torch.full((b.S * w.k,), float("nan"), device=DEV) for _ in workers]
+    for g, c in zip(workers, comps):
+        b.compress(g, w.N, c)
+    total = torch.full((b.S * w.k,), float("nan"), device=DEV)
+    b.aggregate(comps, total)
+    out32 = torch.full((w.M,), float("nan"), device=DEV)
+    b.decompress(total, out32, "f32")
+    out_native = None
+    if w.dtype == "bf16":
+        out_native = torch.empty(w.M, device=DEV, dtype=torch.bfloat16)
+        b.decompress(total, out_native, "bf16")
+    torch.cuda.synchronize()
+
+    # ---- every element, against float64 PyTorch -------------------------------------------
+    y0 = _torch_reference(w, U64, mu64, workers[0], w.N)
+    assert _rel(comps[0].double().view(b.S, w.k), y0) < REL_TOL
+    ylast = _torch_reference(w, U64, mu64, workers[-1], w.N)
+    assert _rel(comps[-1].double().view(b.S, w.k), ylast) < REL_TOL
+    del y0, ylast
+    acc = torch.zeros_like(total, dtype=torch.float64)
+    for c in comps:
+        acc += c.double()
+    assert _rel(total.double(), acc) < 1e-6
+    del acc
+    ref_out = _torch_decompress(w, U64, mu64, total.double().view(b.S, w.k))
+    assert _rel(out32.double(), ref_out) < REL_TOL
+    assert float((out32.double() - ref_out).abs().max()) < REL_TOL * float(ref_out.abs().max())
+    if out_native is not None:
+        assert _rel(out_native.double(), ref_out) < 2.0 ** -8
+    del ref_out
+
+    # ---- sampled slice ranges, against the oracle -----------------------------------------------
+    for (j0, j1) in _ranges(w, blocks, rng):
+        ok = _in_blocks(w, blocks, j0, j1)
+        lo, hi = j0 * w.d, min(j1 * w.d, w.M)
+        sub_offs, Us, mus = _sub_problem(w, U64, mu64, j0, j1)
+        ys = []
+        for g, c in zip(workers, comps):
+            y = oracle.compress(synth.to_numpy(g[lo:hi]), Us, mus, w.N, dtype=w.dtype, offsets=sub_offs)
+            got = c[j0 * w.k:j1 * w.k].cpu().numpy().reshape(-1, w.k)
+            assert_close(got[ok], y[ok], REL_TOL, f"{name} compress slices [{j0},{j1})")
+            ys.append(y)
+        Y = oracle.aggregate(ys)
+        got = total[j0 * w.k:j1 * w.k].cpu().numpy().reshape(-1, w.k)
+        assert_close(got[ok], Y[ok], REL_TOL, f"{name} aggregate slices [{j0},{j1})")
+        xh = oracle.decompress(got.astype(np.float64), Us, mus, hi - lo, offsets=sub_offs)
+        got_x = out32[lo:hi].cpu().numpy()
+        okx = np.repeat(ok, w.d)[: hi - lo]
+        assert_close(got_x[okx], xh[okx], REL_TOL, f"{name} decompress slices [{j0},{j1})")
+    b.close()
+
+
+def _sub_problem(w, U64, mu64, j0, j1):
+    """The slices [j0, j1) as a gradient of their own: its basis offsets, U and mu."""
+    offs = w.block_offsets()
+    if offs is None:
+        return None, U64, mu64
+    b0 = max(b for b in range(w.n_blocks) if offs[b] <= j0)
+    b1 = max(b for b in range(w.n_blocks) if offs[b] < j1)
+    sub = [0] + [offs[b] - j0 for b in range(b0 + 1, b1 + 1)] + [j1 - j0]
+    return sub, U64[b0:b1 + 1], mu64[b0:b1 + 1]
+
+
+FIT_L = {"tiny": 8, "resnet50": 16, "alexnet": 6, "vgg16": 3, "vgg16_bf16": 2}
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_fullsize_fit(name):
+    w = WORKLOADS[name]
+    L = FIT_L[name]
+    rng = np.random.default_rng(w.seed)
+    blocks = _sample_blocks(w)
+    fit = synth.fit_gradients(w, DEV, L=L)
+    b = gvq.Basis(w.M, w.d, w.k, w.block_offsets(), w.dtype)
+    b.fit(fit)
+    sweeps = b.fit_status()
+    assert 0 < sweeps < 40
+    U, mu, eig = b.export()
+    C, n = b.export_cov()
+    b.close()
+    fit_np = [synth.to_numpy(g) for g in fit]
+    del fit
+    Uo, muo, eigo = _oracle_basis_on_blocks(w, fit_np, blocks, rng)
+
+    offs = w.block_offsets() or [0, w.S]
+    full = w.M // w.d
+    for bb in range(w.n_blocks):
+        # invariants of every basis, from the library's own covariance
+        Ub = U[bb].astype(np.float64)
+        lam1 = eig[bb][0]
+        assert n[bb] == max(0, min(offs[bb + 1], full) - offs[bb]) * L
+        assert np.max(np.abs(Ub.T @ Ub - np.eye(w.k))) < 1e-5
+        assert np.max(np.abs(C[bb] @ Ub - Ub * eig[bb][: w.k])) < 1e-6 * lam1
+        assert abs(eig[bb].sum() - np.trace(C[bb])) < 1e-10 * lam1
+        assert np.all(np.diff(eig[bb]) <= 0)
+    for bb in blocks:
+        lam1 = eigo[bb][0]
+        np.testing.assert_allclose(eig[bb], eigo[bb], rtol=0, atol=1e-10 * lam1)
+        np.testing.assert_allclose(mu[bb], muo[bb], rtol=2e-7, atol=1e-7 * np.sqrt(lam1))
+        assert max_angle(U[bb].astype(np.float64), Uo[bb]) < ANGLE_TOL
+        # a few covariance entries, recomputed one by one by the oracle
+        lo, hi = offs[bb] * w.d, min(offs[bb + 1] * w.d, w.M)
+        sub = [g[lo:hi] for g in fit_np]
+        for (i, j) in [(0, 0), (1, w.d - 1), (w.d // 2, w.d // 3)]:
+            ref = oracle.cov_entry(sub, w.d, i, j, dtype=w.dtype)
+            assert abs(C[bb][i, j] - ref) < 1e-11 * lam1
