@@ -28,6 +28,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run gvq_aggregate with ONE input three times: a plain "
+                         "copy of S*k floats, the known-size kernel that HBM byte counters are scaled by")
     ap.add_argument("--fit-gradients", type=int, default=None,
                     help="override L (gradients the basis is fitted on)")
     args = ap.parse_args()
@@ -113,6 +116,11 @@ def main():
     ms_per_step = max(wall_ms, dev_ms)
     value = grad_bytes / ms_per_step / 1e6                # GB/s of gradient through the path
     eff = path_bytes / ms_per_step / 1e6
+
+    if args.calibration_copy:
+        for _ in range(3):
+            basis.aggregate(comps[:1], total)
+        torch.cuda.synchronize()
 
     # reconstruction quality (the paper's loss ||ghat - g||^2 / ||g||^2), as a sanity number
     gsum = torch.zeros(w.M, device=dev, dtype=torch.float64)

@@ -153,15 +153,28 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs 
     constexpr int NQ = CPS / 4;                   // 128-bit LDS reads per lane per tile
     constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
 
+    constexpr int KC = 4 * NT;                    // 128-bit chunks per slice of the padded result tile
+
     __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
+    __shared__ f4 ldso_all[WAVES_PER_WG][TILE_SLICES * KC];
     const int lane = threadIdx.x & 63;
     f4* lds = lds_all[threadIdx.x >> 6];
+    f4* ldso = ldso_all[threadIdx.x >> 6];
 
     const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
     TileIter it;
     if (!it.init(T, a.run_tiles)) return;
 
     const int n_ = lane & 15, kk = lane >> 4;
+    // result tile in memory order: 16 slices x k floats, contiguous; this lane's 128-bit pieces
+    const int kc = a.k >> 2;
+    int so_s[NT], so_c[NT];
+#pragma unroll
+    for (int r = 0; r < NT; ++r) {
+        const int g = r * 64 + lane;
+        so_s[r] = kc ? g / kc : 0;
+        so_c[r] = kc ? g - so_s[r] * kc : 0;
+    }
     const int lc = lane % LCPS;                   // this lane's load chunk within a slice
     const bool loads = lane < TILE_LOADS;         // false only for the upper lanes at D = 16, bf16
 
@@ -275,15 +288,25 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs 
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[q][j], acc[nt], 0, 0, 0);
             // lane holds comps 16*nt + 4*kk + r of slice s0 + n_
-            const int64_t j = s0 + n_;
             const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
-            if (j >= lo && j < hi) {
-                float* o = (float*)a.out + j * a.k;
-                if ((a.k & 3) == 0) {
+            if ((a.k & 3) == 0) {
+                // through LDS, so that the tile leaves as full-width stores in memory order
+                wave_lds_sync();
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        if (16 * nt + 4 * kk < a.k) stream_store((f4*)(o + 16 * nt + 4 * kk), acc[nt]);
-                } else {
+                for (int nt = 0; nt < NT; ++nt) ldso[n_ * KC + ((4 * nt + kk) ^ swz<16 * NT>(n_))] = acc[nt];
+                wave_lds_sync();
+                float* o = (float*)a.out + s0 * a.k;
+#pragma unroll
+                for (int r = 0; r < NT; ++r) {
+                    const int g = r * 64 + lane;
+                    const int64_t j = s0 + so_s[r];
+                    if (g < TILE_SLICES * kc && j >= lo && j < hi)
+                        stream_store((f4*)(o + 4 * g), ldso[so_s[r] * KC + (so_c[r] ^ swz<16 * NT>(so_s[r]))]);
+                }
+            } else {
+                const int64_t j = s0 + n_;
+                if (j >= lo && j < hi) {
+                    float* o = (float*)a.out + j * a.k;
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -374,14 +397,31 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
     constexpr int NS = (TILE_STORES + 63) / 64;      // stores per lane per tile
     constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
 
+    constexpr int KC = 4 * NQ;                       // 128-bit chunks per slice of the padded input tile
+
     __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
+    __shared__ f4 ldsi_all[WAVES_PER_WG][TILE_SLICES * KC];
     const int lane = threadIdx.x & 63;
     f4* lds = lds_all[threadIdx.x >> 6];
+    f4* ldsi = ldsi_all[threadIdx.x >> 6];
     const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
     TileIter it;
     if (!it.init(T, a.run_tiles)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const float* Y = (const float*)a.in;
+    const bool vec = (a.k & 3) == 0;
+    // input tile in memory order: 16 slices x k floats, contiguous; this lane's 128-bit pieces
+    const int kc = a.k >> 2;
+    int si_s[NQ], si_c[NQ];
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) {
+        const int g = r * 64 + lane;
+        si_s[r] = kc ? g / kc : 0;
+        si_c[r] = kc ? g - si_s[r] * kc : 0;
+    }
+    // columns k..KP of the padded tile are never written: they must read as zero
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) ldsi[r * 64 + lane] = f4{0.f, 0.f, 0.f, 0.f};
 
     int cur_b = block_of_tile(a, it.t);
     int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
@@ -401,21 +441,26 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
 
     f4 y[NQ];
     auto load_tile = [&](int64_t t) {
+        if (vec) {   // memory order: full-width loads; transposed through LDS later
+            const float* p = Y + t * TILE_SLICES * a.k;
+#pragma unroll
+            for (int r = 0; r < NQ; ++r) {
+                const int g = r * 64 + lane;
+                f4 v = {0.f, 0.f, 0.f, 0.f};
+                if (g < TILE_SLICES * kc && t * TILE_SLICES + si_s[r] < a.S) v = stream_load((const f4*)(p + 4 * g));
+                y[r] = v;
+            }
+            return;
+        }
         const int64_t j = t * TILE_SLICES + n_;
-        const bool vec = (a.k & 3) == 0;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int c0 = 16 * q + 4 * kk;
             f4 v = {0.f, 0.f, 0.f, 0.f};
             if (j < a.S) {
-                const float* p = Y + j * a.k + c0;
-                if (vec) {
-                    if (c0 < a.k) v = stream_load((const f4*)p);
-                } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (c0 + r < a.k) v[r] = p[r];
-                }
+                for (int r = 0; r < 4; ++r)
+                    if (c0 + r < a.k) v[r] = Y[j * a.k + c0 + r];
             }
             y[q] = v;
         }
@@ -433,8 +478,18 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
             load_basis(cur_b);
         }
         f4 yc[NQ];
+        if (vec) {
+            wave_lds_sync();
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) yc[q] = y[q];
+            for (int r = 0; r < NQ; ++r)
+                if (r * 64 + lane < TILE_SLICES * kc) ldsi[si_s[r] * KC + (si_c[r] ^ swz<16 * NQ>(si_s[r]))] = y[r];
+            wave_lds_sync();
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) yc[q] = ldsi[n_ * KC + ((4 * q + kk) ^ swz<16 * NQ>(n_))];
+        } else {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) yc[q] = y[q];
+        }
         more = it.advance();
         if (more) load_tile(it.t);
 
