@@ -56,7 +56,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_mom, h->d_sweeps};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
@@ -101,10 +101,23 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipGetDevice(&h->device));
         TRY(hipGetDeviceProperties(&prop, h->device));
         h->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-        int64_t P = (4LL * h->num_cu + n_blocks - 1) / n_blocks;
-        if (P > (longest + 63) / 64) P = (longest + 63) / 64;
-        if (P < 1) P = 1;
-        h->P = (int)P;
+        size_t width = (size_t)d * d + d;
+        if (gvq_moments_mfma_shape(d)) {
+            // two work-groups of 4 waves per compute unit, spread over the bases; never less
+            // than 64 sample slices per stream
+            const int streams = gvq_moments_streams(d);
+            int64_t wgs = (2LL * h->num_cu + n_blocks - 1) / n_blocks;
+            if (wgs > (longest + 64LL * streams - 1) / (64LL * streams)) wgs = (longest + 64LL * streams - 1) / (64LL * streams);
+            if (wgs < 1) wgs = 1;
+            h->mom_wgs = (int)wgs;
+            h->P = (int)wgs * streams;
+            width = (size_t)gvq_moments_packed_width(d);
+        } else {
+            int64_t P = (4LL * h->num_cu + n_blocks - 1) / n_blocks;
+            if (P > (longest + 63) / 64) P = (longest + 63) / 64;
+            if (P < 1) P = 1;
+            h->P = (int)P;
+        }
         const size_t B = (size_t)n_blocks, W = (size_t)d * d + d, n = (size_t)(d + (d & 1));
         TRY(hipMalloc((void**)&h->d_offs, sizeof(int64_t) * (B + 1)));
         TRY(hipMalloc((void**)&h->d_U, sizeof(float) * B * d * k));
@@ -117,7 +130,8 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
         TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
-        TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * W));
+        TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * width));
+        TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));
         TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
         TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
         TRY(hipMemcpy(h->d_offs, h->h_offs, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));

@@ -115,6 +115,219 @@ __global__ void reduce_partials_kernel(const double* part, double* mom, int P, i
 }
 
 // --------------------------------------------------------------------------------------
+// moments on the fp64 matrix pipe, d in {16,32,64,128}.
+//
+// sum x x^T over samples is a (d x n)(n x d) product with the samples as the contraction
+// index, so v_mfma_f64_16x16x4_f64 fits directly: A and B operands have the same lane layout
+// (lane l holds row/column l%16 for contraction step l/16), i.e. lane (m, kk) holds element m
+// of a 16-element tile of sample kk of the current group of 4 samples -- both operands of a
+// tile pair come from the same registers.  Result register r of lane l is entry
+// (row 4r + l/16, column l%16) of the 16x16 block.  Only tile pairs T1 <= T2 are computed (the
+// matrix is symmetric): 36 blocks at d = 128, all held in one wave's accumulators (288
+// registers, which is why a wave has a SIMD to itself here); the four waves of a work-group
+// take different samples.
+// A "tile" is any 16 elements, so it is chosen to suit the loads: for d >= 64 a lane loads
+// 128-bit chunk m + 16q of its sample's slice and register c of that chunk belongs to tile
+// T = 4q + c, whose element m is 4(m + 16q) + c; for d < 64 tile T is elements 16T..16T+15.
+// Packed partial layout per wave: [pair][r][lane] blocks of 256 doubles, then the d sums.
+// --------------------------------------------------------------------------------------
+typedef double d4 __attribute__((ext_vector_type(4)));
+typedef unsigned int mu4 __attribute__((ext_vector_type(4)));
+typedef unsigned int mu2 __attribute__((ext_vector_type(2)));
+
+__host__ __device__ constexpr int mom_pairs(int D) { return (D / 16) * (D / 16 + 1) / 2; }
+__host__ __device__ constexpr int mom_packed_width(int D) { return mom_pairs(D) * 256 + D; }
+// element index of entry m of tile T
+__host__ __device__ inline int mom_elem(int D, int T, int m)
+{
+    return D >= 64 ? 4 * (m + 16 * (T / 4)) + (T % 4) : 16 * T + m;
+}
+
+struct MomMfmaArgs {
+    gvq_ptrs grads;
+    int L;
+    const int64_t* offs;
+    int64_t M;
+    int wgs;         // work-groups per basis (each holds 4 sample streams, 2 at d = 128)
+    int accumulate;  // 0: overwrite the partials, 1: add to them
+    double* part;    // [B][wgs * streams][packed width]
+};
+
+// HALF selects which tile pairs this wave accumulates: with SPLIT = 2 (d = 128) the 36 pairs
+// are shared by two waves that read the same samples (pairs 0..17 and 18..35), so that the
+// accumulators of one wave fit the accumulation registers; otherwise every wave has all pairs.
+template <int D, bool BF16, int SPLIT, int HALF>
+__device__ __forceinline__ void moments_mfma_body(const MomMfmaArgs& a, int stream, int nstreams)
+{
+    constexpr int NTL = D / 16, NPAIR = mom_pairs(D), WP = mom_packed_width(D);
+    constexpr int P0 = SPLIT == 2 ? (HALF ? NPAIR / 2 : 0) : 0;          // first pair of this wave
+    constexpr int P1 = SPLIT == 2 ? (HALF ? NPAIR : NPAIR / 2) : NPAIR;  // one past its last pair
+    constexpr int NLD = D >= 64 ? D / 64 : NTL;   // loads per lane per sample group
+    const int lane = threadIdx.x & 63;
+    const int m = lane & 15, kk = lane >> 4;
+    const int b = blockIdx.y, p = blockIdx.x;
+
+    const int64_t full = a.M / D;
+    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
+    if (hi < lo) hi = lo;
+    const int64_t cnt = hi - lo;
+    const int64_t nw = (int64_t)a.wgs * nstreams, w = (int64_t)p * nstreams + stream;
+    const int64_t j0 = lo + cnt * w / nw, j1 = lo + cnt * (w + 1) / nw;   // this wave's samples
+
+    d4 acc[P1 - P0];
+    double sacc[NTL];
+#pragma unroll
+    for (int i = 0; i < P1 - P0; ++i) acc[i] = d4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < NTL; ++i) sacc[i] = 0.0;
+
+    // raw loads of one group of 4 samples: this lane's sample is j = first + kk
+    auto load_group = [&](const void* g, int64_t first, float (&x)[NTL]) {
+        const int64_t j = first + kk;
+        const bool ok = j < j1;
+        if (D >= 64) {
+#pragma unroll
+            for (int q = 0; q < NLD; ++q) {
+                const int64_t e = j * D + 4 * (m + 16 * q);
+                if (BF16) {
+                    mu2 v = {0u, 0u};
+                    if (ok) v = *(const mu2*)((const unsigned short*)g + e);
+                    x[4 * q + 0] = __uint_as_float(v.x << 16);
+                    x[4 * q + 1] = __uint_as_float(v.x & 0xffff0000u);
+                    x[4 * q + 2] = __uint_as_float(v.y << 16);
+                    x[4 * q + 3] = __uint_as_float(v.y & 0xffff0000u);
+                } else {
+                    mu4 v = {0u, 0u, 0u, 0u};
+                    if (ok) v = *(const mu4*)((const float*)g + e);
+                    x[4 * q + 0] = __uint_as_float(v.x);
+                    x[4 * q + 1] = __uint_as_float(v.y);
+                    x[4 * q + 2] = __uint_as_float(v.z);
+                    x[4 * q + 3] = __uint_as_float(v.w);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int T = 0; T < NTL; ++T) {
+                const int64_t e = j * D + 16 * T + m;
+                float v = 0.f;
+                if (ok) v = BF16 ? __uint_as_float((unsigned int)((const unsigned short*)g)[e] << 16)
+                                 : ((const float*)g)[e];
+                x[T] = v;
+            }
+        }
+    };
+    auto consume = [&](const float (&x)[NTL]) {
+        double xd[NTL];
+#pragma unroll
+        for (int T = 0; T < NTL; ++T) {
+            xd[T] = (double)x[T];
+            if (HALF == 0) sacc[T] += xd[T];
+        }
+        int pi = 0;
+#pragma unroll
+        for (int T1 = 0; T1 < NTL; ++T1)
+#pragma unroll
+            for (int T2 = T1; T2 < NTL; ++T2) {
+                if (pi >= P0 && pi < P1)
+                    acc[pi - P0] = __builtin_amdgcn_mfma_f64_16x16x4f64(xd[T1], xd[T2], acc[pi - P0], 0, 0, 0);
+                ++pi;
+            }
+    };
+
+    for (int l = 0; l < a.L; ++l) {
+        const void* g = a.grads.p[l];
+        float xa[NTL], xb[NTL], na[NTL], nb[NTL];
+        int64_t j = j0;
+        if (j < j1) {
+            load_group(g, j, xa);
+            load_group(g, j + 4, xb);
+        }
+        for (; j < j1; j += 8) {
+            load_group(g, j + 8, na);     // two groups ahead; past the range they read as zero
+            load_group(g, j + 12, nb);
+            consume(xa);
+            consume(xb);
+#pragma unroll
+            for (int T = 0; T < NTL; ++T) { xa[T] = na[T]; xb[T] = nb[T]; }
+        }
+    }
+
+    double* out = a.part + ((size_t)b * nw + w) * WP;
+#pragma unroll
+    for (int pi = P0; pi < P1; ++pi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double* o = out + pi * 256 + r * 64 + lane;
+            *o = a.accumulate ? *o + acc[pi - P0][r] : acc[pi - P0][r];
+        }
+    if (HALF == 0) {
+        // sums: add the four sample lanes kk of every element
+#pragma unroll
+        for (int T = 0; T < NTL; ++T) {
+            double v = sacc[T];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (kk == 0) {
+                double* o = out + NPAIR * 256 + T * 16 + m;
+                *o = a.accumulate ? *o + v : v;
+            }
+        }
+    }
+}
+
+template <int D, bool BF16>
+__global__ __launch_bounds__(256, 2) void moments_mfma_kernel(MomMfmaArgs a)
+{
+    const int wave = threadIdx.x >> 6;
+    if constexpr (D == 128) {
+        if (wave & 1) moments_mfma_body<D, BF16, 2, 1>(a, wave >> 1, 2);
+        else moments_mfma_body<D, BF16, 2, 0>(a, wave >> 1, 2);
+    } else {
+        moments_mfma_body<D, BF16, 1, 0>(a, wave, 4);
+    }
+}
+
+// dst[b][g][i] = src[b][g*G][i] + src[b][g*G+1][i] + ... (at most G terms, fixed order)
+__global__ void reduce_groups_kernel(const double* src, double* dst, int P, int G, int W)
+{
+    const int b = blockIdx.z, g = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= W) return;
+    const int nG = (P + G - 1) / G;
+    const int p0 = g * G, p1 = p0 + G < P ? p0 + G : P;
+    const double* s = src + ((size_t)b * P + p0) * W + i;
+    double acc = 0.0;
+    for (int p = p0; p < p1; ++p, s += W) acc += *s;
+    dst[((size_t)b * nG + g) * W + i] = acc;
+}
+
+// packed [B][packed width] -> mom [B][d*d + d] (both triangles written)
+__global__ void unpack_moments_kernel(const double* packed, double* mom, int D)
+{
+    const int b = blockIdx.y;
+    const int NTL = D / 16, NPAIR = NTL * (NTL + 1) / 2, WP = NPAIR * 256 + D;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= WP) return;
+    const double v = packed[(size_t)b * WP + i];
+    double* o = mom + (size_t)b * (D * D + D);
+    if (i >= NPAIR * 256) {
+        const int t = i - NPAIR * 256;
+        o[D * D + mom_elem(D, t / 16, t % 16)] = v;
+        return;
+    }
+    int pi = i / 256, rem = i % 256, r = rem / 64, lane = rem % 64;
+    int T1 = 0, T2 = 0, c = 0;
+    for (int t1 = 0; t1 < NTL; ++t1)
+        for (int t2 = t1; t2 < NTL; ++t2) {
+            if (c == pi) { T1 = t1; T2 = t2; }
+            ++c;
+        }
+    const int e1 = mom_elem(D, T1, 4 * r + lane / 16), e2 = mom_elem(D, T2, lane % 16);
+    o[e1 * D + e2] = v;
+    if (T1 != T2) o[e2 * D + e1] = v;
+}
+
+// --------------------------------------------------------------------------------------
 // Eigensolver: two-sided Jacobi with the round-robin ("chess tournament") ordering.  In one
 // step the n/2 disjoint index pairs (p_i, q_i) are rotated at once: A <- J^T A J with J the
 // product of the n/2 plane rotations, which maps every 2x2 block A[{p_i,q_i}][{p_j,q_j}] to
@@ -220,6 +433,19 @@ __global__ void eigen_kernel(EigArgs a)
                 pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
             }
             __syncthreads();
+            // eigenvector pairs of this round: start their (global memory) loads first, so the
+            // latency runs under the LDS work on the matrix; at most 8 pairs per thread for
+            // every launch shape used (n*half <= 8 * blockDim)
+            double vr[8], vt[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = tid + u * nth;
+                if (idx < n * half) {
+                    const int row = idx / half, j = idx - row * half;
+                    vr[u] = V[row * n + pp[j]];
+                    vt[u] = V[row * n + qq[j]];
+                }
+            }
             for (int idx = tid; idx < half * half; idx += nth) {
                 const int i = idx / half, j = idx - i * half;
                 const int p = pp[i], q = qq[i], r = pp[j], t = qq[j];
@@ -234,13 +460,15 @@ __global__ void eigen_kernel(EigArgs a)
                 if (i == j) { ypt = 0.0; yqr = 0.0; }
                 A[p * n + r] = ypr; A[p * n + t] = ypt; A[q * n + r] = yqr; A[q * n + t] = yqt;
             }
-            for (int idx = tid; idx < n * half; idx += nth) {
-                const int row = idx / half, j = idx - row * half;
-                const int r = pp[j], t = qq[j];
-                const double cj = cs[j], sj = sn[j];
-                double vr = V[row * n + r], vt = V[row * n + t];
-                V[row * n + r] = cj * vr - sj * vt;
-                V[row * n + t] = sj * vr + cj * vt;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = tid + u * nth;
+                if (idx < n * half) {
+                    const int row = idx / half, j = idx - row * half;
+                    const double cj = cs[j], sj = sn[j];
+                    V[row * n + pp[j]] = cj * vr[u] - sj * vt[u];
+                    V[row * n + qq[j]] = sj * vr[u] + cj * vt[u];
+                }
             }
             __syncthreads();
         }
@@ -293,27 +521,68 @@ size_t gvq_eigen_lds_bytes(int d)
     return sizeof(double) * ((size_t)n * n + 2 * half + 32 + n) + sizeof(int) * (2 * half + n);
 }
 
+template <int D>
+static void launch_moments_mfma(const gvq_basis* h, const MomMfmaArgs& a, hipStream_t st)
+{
+    dim3 grid(h->mom_wgs, h->B);
+    if (h->dtype == GVQ_BF16)
+        hipLaunchKernelGGL((moments_mfma_kernel<D, true>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((moments_mfma_kernel<D, false>), grid, dim3(256), 0, st, a);
+}
+
+bool gvq_moments_mfma_shape(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+int gvq_moments_packed_width(int d) { return mom_packed_width(d); }
+int gvq_moments_streams(int d) { return d == 128 ? 2 : 4; }
+
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st)
 {
     const int d = h->d, W = d * d + d;
-    const int64_t npart = (int64_t)h->B * h->P * W;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, st, h->d_part, npart);
-    GVQ_HIP(hipGetLastError());
-
-    for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
-        MomArgs a;
-        a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
-        for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
-        a.offs = h->d_offs; a.M = h->M; a.d = d; a.P = h->P; a.part = h->d_part;
-        if (d <= 16) launch_moments<1>(h, a, st);
-        else if (d <= 32) launch_moments<2>(h, a, st);
-        else if (d <= 64) launch_moments<4>(h, a, st);
-        else launch_moments<8>(h, a, st);
+    if (gvq_moments_mfma_shape(d)) {
+        const int WP = mom_packed_width(d);
+        for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
+            MomMfmaArgs a;
+            a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
+            for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
+            a.offs = h->d_offs; a.M = h->M; a.wgs = h->mom_wgs; a.accumulate = l0 > 0; a.part = h->d_part;
+            switch (d) {
+            case 16: launch_moments_mfma<16>(h, a, st); break;
+            case 32: launch_moments_mfma<32>(h, a, st); break;
+            case 64: launch_moments_mfma<64>(h, a, st); break;
+            default: launch_moments_mfma<128>(h, a, st); break;
+            }
+            GVQ_HIP(hipGetLastError());
+        }
+        // fixed-order tree: P partials -> groups of 32 -> one, then to the d x d layout
+        const int P = h->P, G = 32, nG = (P + G - 1) / G;
+        hipLaunchKernelGGL(reduce_groups_kernel, dim3((WP + 255) / 256, nG, h->B), dim3(256), 0, st,
+                           h->d_part, h->d_part2, P, G, WP);
+        GVQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(reduce_groups_kernel, dim3((WP + 255) / 256, 1, h->B), dim3(256), 0, st,
+                           h->d_part2, h->d_part, nG, nG, WP);   // result: d_part[b][0][:] with stride WP
+        GVQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(unpack_moments_kernel, dim3((WP + 255) / 256, h->B), dim3(256), 0, st,
+                           h->d_part, h->d_mom, d);
+        GVQ_HIP(hipGetLastError());
+    } else {
+        const int64_t npart = (int64_t)h->B * h->P * W;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, st, h->d_part, npart);
+        GVQ_HIP(hipGetLastError());
+        for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
+            MomArgs a;
+            a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
+            for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
+            a.offs = h->d_offs; a.M = h->M; a.d = d; a.P = h->P; a.part = h->d_part;
+            if (d <= 16) launch_moments<1>(h, a, st);
+            else if (d <= 32) launch_moments<2>(h, a, st);
+            else if (d <= 64) launch_moments<4>(h, a, st);
+            else launch_moments<8>(h, a, st);
+            GVQ_HIP(hipGetLastError());
+        }
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((W + 255) / 256, h->B), dim3(256), 0, st,
+                           h->d_part, h->d_mom, h->P, W);
         GVQ_HIP(hipGetLastError());
     }
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((W + 255) / 256, h->B), dim3(256), 0, st,
-                       h->d_part, h->d_mom, h->P, W);
-    GVQ_HIP(hipGetLastError());
 
     EigArgs e;
     e.mom = h->d_mom; e.offs = h->d_offs; e.M = h->M; e.L = L; e.d = d; e.k = h->k;

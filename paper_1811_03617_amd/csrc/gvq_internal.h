@@ -23,7 +23,9 @@ struct gvq_basis {
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
     double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
-    double* d_part = nullptr;   // [B][P][d*d+d] per-workgroup moment partials
+    double* d_part = nullptr;   // [B][P][width] moment partials (width: d*d+d, or the packed width of the MFMA path)
+    double* d_part2 = nullptr;  // [B][ceil(P/32)][width] second level of the partial sum (MFMA path)
+    int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
     int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
     int P = 0;                  // moment partials per basis
@@ -61,3 +63,6 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st
 // Refresh the operand-order copies of U after d_U changed (no-op for non-MFMA shapes).
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st);
 bool gvq_mfma_shape(int d, int k);
+bool gvq_moments_mfma_shape(int d);
+int gvq_moments_packed_width(int d);
+int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
