@@ -51,6 +51,10 @@ def lib():
         L.gvq_oracle_aggregate.restype = None
         L.gvq_oracle_decompress.argtypes = [dp, i32, i32, i32, C.POINTER(i64), dp, dp, i64, i64, dp]
         L.gvq_oracle_decompress.restype = None
+        L.gvq_oracle_select_k.argtypes = [dp, i32, C.c_double]
+        L.gvq_oracle_select_k.restype = i32
+        L.gvq_oracle_local_loss.argtypes = [vp, i64, i32, i32, i32, i32, C.POINTER(i64), dp, dp, i32, dp]
+        L.gvq_oracle_local_loss.restype = None
         _lib = L
     return _lib
 
@@ -210,3 +214,29 @@ def decompress(Y, U, mu, M, offsets=None, j0=0, j1=None):
     out = out.reshape(-1)
     valid = min(M, j1 * d) - j0 * d
     return out[:valid]
+
+
+def select_k(eig, lam):
+    """Eq. (5): smallest k whose leading eigenvalues hold at least 1 - lam of the total.
+    eig: [d] or [B, d] (descending); returns an int or a list of ints."""
+    e = np.ascontiguousarray(eig, dtype=np.float64)
+    if e.ndim == 1:
+        return lib().gvq_oracle_select_k(_dptr(e), e.shape[0], float(lam))
+    return [lib().gvq_oracle_select_k(_dptr(np.ascontiguousarray(row)), e.shape[1], float(lam)) for row in e]
+
+
+def local_loss(grad, U, mu, n_workers, dtype="f32", offsets=None):
+    """Eq. (6): per-basis || g_n - (U g'_n + mu/N) ||^2 of one worker's gradient, [B] float64."""
+    g = _grad(grad, dtype)
+    M = g.shape[0]
+    U = np.asarray(U)
+    d, k = U.shape[-2], U.shape[-1]
+    if d > MAX_D:
+        raise ValueError("d too large for the oracle")
+    o = _offsets(offsets, num_slices(M, d))
+    B = len(o) - 1
+    U, mu = _basis_args(U, mu, d, k, B)
+    out = np.empty(B, dtype=np.float64)
+    lib().gvq_oracle_local_loss(g.ctypes.data, M, d, k, _DT[dtype], B, _optr(o), _dptr(U), _dptr(mu),
+                                int(n_workers), _dptr(out))
+    return out

@@ -382,3 +382,60 @@ void gvq_oracle_decompress(const double *Y, int d, int k, int n_blocks, const in
         }
     }
 }
+
+/* ------------------------------------------------------------------------------------
+ * Section 3, "Compressor dimension" (Eq. 5): the smallest k such that
+ *     (eig[0] + ... + eig[k-1]) / (eig[0] + ... + eig[d-1]) >= 1 - lambda,
+ * eig in decreasing order, 0 <= lambda < 1.  Partial sums are taken from the largest
+ * eigenvalue down, in double.  If the total is not positive (no sample, or all-zero
+ * data) there is nothing to lose and the answer is 1.
+ * ---------------------------------------------------------------------------------- */
+int gvq_oracle_select_k(const double *eig, int d, double lambda)
+{
+    double total = 0.0;
+    for (int i = 0; i < d; ++i) total += eig[i];
+    if (!(total > 0.0)) return 1;
+    double cum = 0.0;
+    for (int k = 1; k <= d; ++k) {
+        cum += eig[k - 1];
+        if (cum / total >= 1.0 - lambda) return k;
+    }
+    return d;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Section 3, "Number of compressed iterations" (Eq. 6): the local compression loss of one
+ * worker,  || g_n - (U g'_n + mu/N) ||^2  with g'_n = U^T (g_n - mu/N)  (Eq. 2),
+ * summed per basis over the slices of its range.  The tail slice is compressed
+ * zero-padded like everywhere else, but only its real elements (index < M) are part of
+ * g_n and enter the norm.  loss[n_blocks].
+ * ---------------------------------------------------------------------------------- */
+void gvq_oracle_local_loss(const void *grad, int64_t M, int d, int k, int dtype, int n_blocks,
+                           const int64_t *offs, const double *U, const double *mu,
+                           int n_workers, double *loss)
+{
+    int64_t S = (M + d - 1) / d;
+    for (int b = 0; b < n_blocks; ++b) {
+        const double *Ub = U + (size_t)b * d * k, *mub = mu + (size_t)b * d;
+        double acc = 0.0;
+        int64_t j0 = offs[b], j1 = offs[b + 1] < S ? offs[b + 1] : S;
+#pragma omp parallel for schedule(static) reduction(+ : acc)
+        for (int64_t j = j0; j < j1; ++j) {
+            double x[512], y[512];
+            load_slice(grad, dtype, M, d, j, x);
+            for (int e = 0; e < d; ++e) x[e] -= mub[e] / (double)n_workers;
+            for (int i = 0; i < k; ++i) {
+                double a = 0.0;
+                for (int e = 0; e < d; ++e) a += Ub[e * k + i] * x[e];
+                y[i] = a;
+            }
+            for (int e = 0; e < d; ++e) {
+                if (j * (int64_t)d + e >= M) break;
+                double r = x[e];            /* (g - mu/N) - U y  ==  g - (U y + mu/N) */
+                for (int i = 0; i < k; ++i) r -= Ub[e * k + i] * y[i];
+                acc += r * r;
+            }
+        }
+        loss[b] = acc;
+    }
+}

@@ -293,3 +293,79 @@ def test_block_with_no_full_slice_gets_unit_vectors():
     U, mu, eig = oracle.fit(fitg, d, k, offsets=[0, 10, 11])
     np.testing.assert_array_equal(U[1], np.eye(d, k))
     assert np.all(mu[1] == 0) and np.all(eig[1] == 0)
+
+
+# ---------------------------------------------------------------- Eq. (5) and Eq. (6)
+def test_select_k_closed_forms():
+    """Eq. (5) on spectra where the answer is obvious."""
+    eig = np.array([8.0, 1.0, 0.5, 0.5])          # total 10
+    assert oracle.select_k(eig, 0.25) == 1         # 8/10 >= 0.75
+    assert oracle.select_k(eig, 0.2) == 1          # 0.8 >= 0.8 (boundary counts)
+    assert oracle.select_k(eig, 0.15) == 2         # 0.9 >= 0.85
+    assert oracle.select_k(eig, 0.05) == 3         # 0.95 >= 0.95
+    assert oracle.select_k(eig, 0.01) == 4
+    assert oracle.select_k(eig, 0.0) == 4
+    assert oracle.select_k(np.array([1.0, 1.0, 1.0, 1.0]), 0.5) == 2
+    assert oracle.select_k(np.zeros(5), 0.01) == 1
+    assert oracle.select_k(np.array([[8.0, 1.0, 0.5, 0.5], [1, 1, 1, 1]]), 0.25) == [1, 3]
+
+
+def test_select_k_equals_numpy_cumsum_and_is_monotone():
+    rng = np.random.default_rng(9)
+    for d in (2, 7, 32, 128):
+        eig = np.sort(rng.random(d) ** 4)[::-1].copy()
+        ks = []
+        for lam in (0.5, 0.1, 0.01, 1e-3, 1e-6):
+            frac = np.cumsum(eig) / eig.sum()
+            want = int(np.argmax(frac >= 1 - lam)) + 1
+            got = oracle.select_k(eig, lam)
+            # summation order differs from numpy's only by rounding: allow the boundary case
+            assert got == want or abs(frac[min(got, want) - 1] - (1 - lam)) < 1e-12
+            ks.append(got)
+        assert ks == sorted(ks)
+
+
+def test_select_k_guarantees_the_loss_bound_on_the_fit_set():
+    """Eq. (5)'s promise: with the selected k, the relative loss on the sample slices is
+    at most lambda (measured with the oracle's own codec)."""
+    w = _tiny()
+    fitg = [synth.to_numpy(g) for g in synth.fit_gradients(w, L=3)]
+    Ufull, mu, eig = oracle.fit(fitg, w.d, w.d)
+    for lam in (0.05, 1e-3):
+        k = oracle.select_k(eig[0], lam)
+        U = Ufull[:, :, :k]
+        lost = sum(oracle.local_loss(g, U, mu, 1)[0] for g in fitg)
+        centred = sum(np.sum((g.astype(np.float64).reshape(-1, w.d) - mu[0]) ** 2) for g in fitg)
+        assert lost / centred <= lam * (1 + 1e-9)
+        if k > 1:
+            lost_less = sum(oracle.local_loss(g, Ufull[:, :, :k - 1], mu, 1)[0] for g in fitg)
+            assert lost_less / centred > lam
+
+
+def test_local_loss_eq6_against_plain_numpy_and_identities():
+    d, k, N = 8, 3, 4
+    rng = np.random.default_rng(21)
+    M = 8 * 50 + 5
+    offs = [0, 20, 51]
+    fitg = [g + np.float32(0.5) for g in _rng_grads(rng, 3, M)]
+    U, mu, _ = oracle.fit(fitg, d, k, offsets=offs)
+    g = _rng_grads(rng, 1, M)[0] * np.float32(2)
+    loss = oracle.local_loss(g, U, mu, N, offsets=offs)
+    # the definition, written with numpy on the zero-padded slices, real elements only
+    gp = np.concatenate([g.astype(np.float64), np.zeros(51 * d - M)]).reshape(51, d)
+    real = (np.arange(51 * d) < M).reshape(51, d)
+    want = []
+    for b in range(2):
+        X = gp[offs[b]:offs[b + 1]] - mu[b] / N
+        R = X - (X @ U[b]) @ U[b].T
+        want.append(np.sum((R ** 2)[real[offs[b]:offs[b + 1]]]))
+    np.testing.assert_allclose(loss, want, rtol=1e-12)
+    # same thing through the oracle's own compress / decompress with mu/N as the offset (N = 1 trick):
+    # g - (U g' + mu/N) with g' = Q(g) is the round-trip error of a single-worker codec whose mean is mu/N
+    y = oracle.compress(g, U, mu / N, 1, offsets=offs)
+    back = oracle.decompress(y, U, mu / N, M, offsets=offs)
+    err = (back - g.astype(np.float64)) ** 2
+    np.testing.assert_allclose(loss, [err[: 20 * d].sum(), err[20 * d:].sum()], rtol=1e-12)
+    # k = d: nothing is lost
+    Uf, muf, _ = oracle.fit(fitg, d, d, offsets=offs)
+    assert np.all(oracle.local_loss(g, Uf, muf, N, offsets=offs) < 1e-24)
