@@ -124,6 +124,27 @@ int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out,
                    gvq_dtype_t out_dtype, void* stream);
 
 /*
+ * Section 3, Eq. (6): the local compression loss of one worker's gradient,
+ *     loss_out[b] = sum over the slices of basis b of || x - (U_b y + mu_b/N) ||^2,
+ *     y = U_b^T (x - mu_b/N)   (Eq. 2),
+ * which a node watches to decide when the basis needs a refresh.  grad: device, M elements
+ * of the handle's dtype; loss_out: device double [B] (8-byte aligned).  The tail slice is
+ * projected zero-padded but only its real elements count.  The gradient is read once;
+ * nothing else of its size is written.  fp32 arithmetic per slice, float64 sums over slices
+ * in a fixed order.  Asynchronous on `stream`.
+ */
+int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out,
+                   void* stream);
+
+/*
+ * Section 3, Eq. (5): for every basis of the last fit, the smallest k such that
+ * (eig[0] + ... + eig[k-1]) / (eig[0] + ... + eig[d-1]) >= 1 - lambda, 0 <= lambda < 1 (1 when
+ * the eigenvalue sum is not positive).  k_out: host int [B].  Advisory: the handle keeps the
+ * k it was created with.  Waits for `stream`.  GVQ_ENOTFIT unless gvq_fit_basis ran.
+ */
+int gvq_select_k(const gvq_basis_t* h, double lambda, int* k_out, void* stream);
+
+/*
  * Copy the basis to host arrays (any may be NULL): U float [B][d][k], mu float [B][d],
  * eig double [B][d].  Synchronises the device.  eig is all zero after gvq_basis_import.
  */

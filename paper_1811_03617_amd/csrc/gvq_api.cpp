@@ -56,7 +56,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
@@ -134,6 +134,12 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));
         TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
         TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
+        TRY(hipMalloc((void**)&h->d_ksel, sizeof(int) * B));
+        TRY(hipMalloc((void**)&h->d_loss_slice, sizeof(float) * (size_t)S));
+        h->loss_groups = (int)((longest + 4095) / 4096);
+        if (h->loss_groups > 256) h->loss_groups = 256;
+        if (h->loss_groups < 1) h->loss_groups = 1;
+        TRY(hipMalloc((void**)&h->d_loss_part, sizeof(double) * B * (size_t)h->loss_groups));
         TRY(hipMemcpy(h->d_offs, h->h_offs, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
         if (n_blocks > 1) {
             const int64_t T = (S + 15) / 16;
@@ -235,6 +241,25 @@ int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out, 
     if (!aligned16(comp_sum) || !aligned16(grad_out)) return GVQ_EALIGN;
     if (!h->fitted) return GVQ_ENOTFIT;
     return gvq_launch_decompress(h, comp_sum, grad_out, out_dtype, (hipStream_t)stream);
+}
+
+int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out, void* stream)
+{
+    if (!h || !grad || !loss_out || n_workers < 1) return GVQ_EINVAL;
+    if (!aligned16(grad) || ((uintptr_t)loss_out & 7u)) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    return gvq_launch_local_loss(h, grad, n_workers, loss_out, (hipStream_t)stream);
+}
+
+int gvq_select_k(const gvq_basis_t* h, double lambda, int* k_out, void* stream)
+{
+    if (!h || !k_out || !(lambda >= 0.0) || !(lambda < 1.0)) return GVQ_EINVAL;
+    if (!h->has_cov) return GVQ_ENOTFIT;
+    int rc = gvq_launch_select_k(h, lambda, (hipStream_t)stream);
+    if (rc != GVQ_OK) return rc;
+    GVQ_HIP(hipStreamSynchronize((hipStream_t)stream));
+    GVQ_HIP(hipMemcpy(k_out, h->d_ksel, sizeof(int) * (size_t)h->B, hipMemcpyDeviceToHost));
+    return GVQ_OK;
 }
 
 int gvq_basis_export(const gvq_basis_t* h, float* U, float* mu, double* eig)

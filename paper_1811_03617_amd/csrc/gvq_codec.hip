@@ -10,118 +10,7 @@
 // Slices always sit on the n side (lane l%16 = slice within a 16-slice tile), so each lane
 // ends with 4 consecutive outputs of one slice in its 4 result registers and stores them
 // as one 128-bit word.
-#include "gvq_internal.h"
-
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-
-#define WAVES_PER_WG 4
-#define WG_THREADS (64 * WAVES_PER_WG)
-#define TILE_SLICES 16
-#ifndef GVQ_NONTEMPORAL
-#define GVQ_NONTEMPORAL 1  // gradients are touched once: keep them out of the way of the caches
-#endif
-
-struct CodecArgs {
-    const void* in;       // compress: gradient; decompress: compressed [S][k]
-    void* out;            // compress: compressed [S][k]; decompress: gradient
-    const float* U;       // [B][d][k]
-    const f4* Upack;      // MFMA-operand order copy of U for this kernel, see pack_basis_kernel
-    const float* mu;      // [B][d]
-    const int64_t* offs;  // [B+1] slice offsets of the bases
-    int64_t M, S;
-    int B, d, k;
-    float n_workers;      // compress only
-    const int* tile_block;  // [T] basis of the first slice of every 16-slice tile (B > 1 only)
-    int run_tiles;        // tile schedule, see TileIter
-};
-
-// Largest b with offs[b] <= j (offs[0] = 0, offs[B] = S > j).
-__device__ __forceinline__ int find_block(const int64_t* offs, int B, int64_t j)
-{
-    int lo = 0, hi = B - 1;
-    while (lo < hi) {
-        int mid = (lo + hi + 1) >> 1;
-        if (offs[mid] <= j) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
-__device__ __forceinline__ float bf16_to_f32(unsigned int hi16)
-{
-    return __uint_as_float(hi16 << 16);
-}
-
-// Round-to-nearest-even fp32 -> bf16 bit pattern (NaN kept quiet).
-__device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
-{
-    unsigned int u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Orders this wave's LDS traffic for the compiler: what one lane wrote is read by another
-// lane of the same wave afterwards.  The hardware executes a wave's LDS instructions in
-// order, so no s_barrier is needed; this only stops the compiler from moving LDS accesses
-// across the exchange point.
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <typename T>
-__device__ __forceinline__ T stream_load(const T* p)
-{
-#if GVQ_NONTEMPORAL
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
-template <typename T>
-__device__ __forceinline__ void stream_store(T* p, T v)
-{
-#if GVQ_NONTEMPORAL
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
-
-// Which tiles a wave works on: runs of R consecutive 16-slice tiles, run r = w, w+W, w+2W, ...
-// for wave w of W.  R = 1 interleaves single tiles, so that at any moment the whole chip
-// reads one compact window of memory (what HBM likes best); a longer run keeps a wave inside
-// one basis for longer when there are many bases; R = ceil(T/W) gives every wave one
-// contiguous chunk.
-struct TileIter {
-    int64_t t, run, run_end, T, W;
-    int R;
-    __device__ __forceinline__ bool init(int64_t T_, int R_)
-    {
-        T = T_; R = R_;
-        W = (int64_t)gridDim.x * WAVES_PER_WG;
-        run = (int64_t)blockIdx.x * WAVES_PER_WG + (threadIdx.x >> 6);
-        t = run * R;
-        run_end = t + R < T ? t + R : T;
-        return t < T;
-    }
-    __device__ __forceinline__ bool advance()
-    {
-        if (++t < run_end) return true;
-        run += W;
-        t = run * R;
-        run_end = t + R < T ? t + R : T;
-        return t < T;
-    }
-};
-
-__device__ __forceinline__ int block_of_tile(const CodecArgs& a, int64_t t)
-{
-    return a.B > 1 ? a.tile_block[t] : 0;
-}
+#include "gvq_device.h"
 
 // --------------------------------------------------------------------------------------
 // compress, MFMA path.  D in {16,32,64,128}, NT = ceil(k/16) in {1,2}.
@@ -136,14 +25,8 @@ __device__ __forceinline__ int block_of_tile(const CodecArgs& a, int64_t t)
 // The contraction index may be visited in any order as long as U follows: MFMA step
 // (q, j) multiplies elements e = 4*(4q + kk) + j, kk = l/16.
 // --------------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ int swz(int s)
-{
-    return (D >= 32) ? (s & 7) : ((s >> 1) & 3);
-}
-
-template <int D, int NT, bool BF16, int VAR>
-__global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs a)
+template <int D, int NT, bool BF16, int VAR, bool LOSS>
+__global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel(CodecArgs a)
 {
     constexpr int CPS = D / 4;                    // fp32 128-bit chunks per slice
     constexpr int EPL = BF16 ? 8 : 4;             // elements per 128-bit global load
@@ -182,6 +65,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs 
     int cur_b = block_of_tile(a, it.t);
     int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
     f4 uf[NQ][NT];   // uf[q][nt][j] = U[4*(4q + kk) + j][16nt + n_], zero past column k
+    f4 ud[LOSS ? NQ : 1][NT];   // LOSS only: ud[et][q][j] = U[16et + n_][16q + 4kk + j]
     float mun[EPL];
 
     auto load_basis = [&](int b) {
@@ -191,6 +75,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs 
         for (int q = 0; q < NQ; ++q)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) uf[q][nt] = Up[(q * NT + nt) * 64];
+        if constexpr (LOSS) {
+            const f4* Up2 = a.Upack2 + (size_t)b * (NQ * NT * 64) + lane;
+#pragma unroll
+            for (int et = 0; et < NQ; ++et)
+#pragma unroll
+                for (int q = 0; q < NT; ++q) ud[et][q] = Up2[(et * NT + q) * 64];
+        }
 #pragma unroll
         for (int i = 0; i < EPL; ++i) mun[i] = mub[lc * EPL + i] / a.n_workers;
     };
@@ -290,7 +181,31 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_mfma_kernel(CodecArgs 
                         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[q][j], acc[nt], 0, 0, 0);
             // lane holds comps 16*nt + 4*kk + r of slice s0 + n_
             const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
-            if ((a.k & 3) == 0 && (VAR & 1) == 0) {
+            if constexpr (LOSS) {
+                // Eq. (6): reconstruct U y from the accumulators (they already sit in the
+                // B-operand order of the second product) and compare with the parked x - mu/N;
+                // x[et][r] and the result register r of tile et are the same element 16et + 4kk + r
+                const int64_t j = s0 + n_;
+                float sq = 0.f;
+#pragma unroll
+                for (int et = 0; et < NQ; ++et) {
+                    f4 rec = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < NT; ++q)
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj)
+                            rec = __builtin_amdgcn_mfma_f32_16x16x4f32(ud[et][q][jj], acc[q][jj], rec, 0, 0, 0);
+                    const int64_t e0 = j * D + 16 * et + 4 * kk;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float df = x[et][r] - rec[r];
+                        if (e0 + r < a.M) sq = fmaf(df, df, sq);   // padding is not part of the gradient
+                    }
+                }
+                sq += __shfl_xor(sq, 16, 64);
+                sq += __shfl_xor(sq, 32, 64);
+                if (kk == 0 && j >= lo && j < hi) ((float*)a.out)[j] = sq;
+            } else if ((a.k & 3) == 0 && (VAR & 1) == 0) {
                 const int64_t j = s0 + n_;
                 if (j >= lo && j < hi) {
                     float* o = (float*)a.out + j * a.k;
@@ -701,7 +616,7 @@ static int run_length(const gvq_basis* h, int64_t tiles, int grid)
 template <int D, int NT, bool BF16, int VAR>
 static int launch_compress_v(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = compress_mfma_kernel<D, NT, BF16, VAR>;
+    auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false>;
     int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
     CodecArgs b = a;
@@ -819,5 +734,137 @@ int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, f
         launch_aggregate_n<AGG_MAX_IN>(n, grid, st, p, out, len);
         GVQ_HIP(hipGetLastError());
     }
+    return GVQ_OK;
+}
+
+
+// ======================================================================================
+// local compression loss (Section 3, Eq. 6)
+// ======================================================================================
+// Any d, k: one wave per slice.  Lanes first share the k projections, then the d residuals.
+template <bool BF16>
+__global__ __launch_bounds__(256) void loss_generic_kernel(CodecArgs a)
+{
+    __shared__ float xs_all[4][GVQ_MAX_D], ys_all[4][GVQ_MAX_D];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float* xs = xs_all[wave];
+    float* ys = ys_all[wave];
+    const int64_t W = (int64_t)gridDim.x * 4;
+    for (int64_t j = (int64_t)blockIdx.x * 4 + wave; j < a.S; j += W) {
+        const int b = find_block(a.offs, a.B, j);
+        const float* Ub = a.U + (size_t)b * a.d * a.k;
+        const float* mub = a.mu + (size_t)b * a.d;
+        wave_lds_sync();
+        for (int e = lane; e < a.d; e += 64) {
+            const int64_t idx = j * a.d + e;
+            float x = 0.f;
+            if (idx < a.M)
+                x = BF16 ? bf16_to_f32(((const unsigned short*)a.in)[idx]) : ((const float*)a.in)[idx];
+            xs[e] = x - mub[e] / a.n_workers;
+        }
+        wave_lds_sync();
+        for (int c = lane; c < a.k; c += 64) {
+            float acc = 0.f;
+            for (int e = 0; e < a.d; ++e) acc = fmaf(Ub[e * a.k + c], xs[e], acc);
+            ys[c] = acc;
+        }
+        wave_lds_sync();
+        float sq = 0.f;
+        for (int e = lane; e < a.d; e += 64) {
+            float r = xs[e];
+            for (int c = 0; c < a.k; ++c) r = fmaf(-Ub[e * a.k + c], ys[c], r);
+            if (j * a.d + e < a.M) sq = fmaf(r, r, sq);
+        }
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off, 64);
+        if (lane == 0) ((float*)a.out)[j] = sq;
+    }
+}
+
+// Fixed-order sum of a block of doubles held one per thread (256 threads).
+__device__ __forceinline__ double wg_sum_256(double v, double* red)
+{
+    red[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    const double tot = red[0];
+    __syncthreads();
+    return tot;
+}
+
+// part[b][g] = sum of the per-slice losses of chunk g (of G) of basis b's slice range
+__global__ __launch_bounds__(256) void loss_reduce1_kernel(const float* per_slice, const int64_t* offs, int G,
+                                                           double* part)
+{
+    __shared__ double red[256];
+    const int b = blockIdx.y, g = blockIdx.x;
+    const int64_t lo = offs[b], cnt = offs[b + 1] - lo;
+    const int64_t j0 = lo + cnt * g / G, j1 = lo + cnt * (g + 1) / G;
+    double acc = 0.0;
+    for (int64_t j = j0 + threadIdx.x; j < j1; j += 256) acc += (double)per_slice[j];
+    acc = wg_sum_256(acc, red);
+    if (threadIdx.x == 0) part[(size_t)b * G + g] = acc;
+}
+
+__global__ __launch_bounds__(256) void loss_reduce2_kernel(const double* part, int G, double* out)
+{
+    __shared__ double red[256];
+    const int b = blockIdx.x;
+    double acc = 0.0;
+    for (int g = threadIdx.x; g < G; g += 256) acc += part[(size_t)b * G + g];
+    acc = wg_sum_256(acc, red);
+    if (threadIdx.x == 0) out[b] = acc;
+}
+
+template <int D, int NT, bool BF16>
+static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    auto kern = compress_mfma_kernel<D, NT, BF16, 0, true>;
+    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    int grid = streaming_grid(h, kern, tiles);
+    CodecArgs b = a;
+    b.run_tiles = run_length(h, tiles, grid);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+template <int D, bool BF16>
+static int launch_loss_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    return h->k <= 16 ? launch_loss_t<D, 1, BF16>(h, a, st) : launch_loss_t<D, 2, BF16>(h, a, st);
+}
+
+int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out, hipStream_t st)
+{
+    CodecArgs a = make_args(h, grad, h->d_loss_slice, n_workers, h->d_Upc);
+    a.Upack2 = (const f4*)h->d_Upd;
+    const bool bf = h->dtype == GVQ_BF16;
+    int rc = GVQ_OK;
+    if (gvq_mfma_shape(h->d, h->k)) {
+        switch (h->d) {
+        case 16: rc = bf ? launch_loss_d<16, true>(h, a, st) : launch_loss_d<16, false>(h, a, st); break;
+        case 32: rc = bf ? launch_loss_d<32, true>(h, a, st) : launch_loss_d<32, false>(h, a, st); break;
+        case 64: rc = bf ? launch_loss_d<64, true>(h, a, st) : launch_loss_d<64, false>(h, a, st); break;
+        default: rc = bf ? launch_loss_d<128, true>(h, a, st) : launch_loss_d<128, false>(h, a, st); break;
+        }
+    } else {
+        int64_t want = (h->S + 3) / 4, cap = (int64_t)h->num_cu * 8;
+        int grid = (int)(want < cap ? want : cap);
+        if (bf)
+            hipLaunchKernelGGL(loss_generic_kernel<true>, dim3(grid), dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(loss_generic_kernel<false>, dim3(grid), dim3(256), 0, st, a);
+        GVQ_HIP(hipGetLastError());
+    }
+    if (rc != GVQ_OK) return rc;
+    const int G = h->loss_groups;
+    hipLaunchKernelGGL(loss_reduce1_kernel, dim3(G, h->B), dim3(256), 0, st, h->d_loss_slice, h->d_offs, G,
+                       h->d_loss_part);
+    GVQ_HIP(hipGetLastError());
+    hipLaunchKernelGGL(loss_reduce2_kernel, dim3(h->B), dim3(256), 0, st, h->d_loss_part, G, loss_out);
+    GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }

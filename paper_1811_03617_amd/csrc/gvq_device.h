@@ -1,0 +1,125 @@
+// Device-side helpers shared by the codec and monitor kernels (gfx950).
+#pragma once
+#include "gvq_internal.h"
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
+#define WAVES_PER_WG 4
+#define WG_THREADS (64 * WAVES_PER_WG)
+#define TILE_SLICES 16
+#ifndef GVQ_NONTEMPORAL
+#define GVQ_NONTEMPORAL 1  // gradients are touched once: keep them out of the way of the caches
+#endif
+
+struct CodecArgs {
+    const void* in;       // compress: gradient; decompress: compressed [S][k]
+    void* out;            // compress: compressed [S][k]; decompress: gradient
+    const float* U;       // [B][d][k]
+    const f4* Upack;      // MFMA-operand order copy of U for this kernel, see pack_basis_kernel
+    const f4* Upack2;     // local-loss kernel only: the decompress-order copy
+    const float* mu;      // [B][d]
+    const int64_t* offs;  // [B+1] slice offsets of the bases
+    int64_t M, S;
+    int B, d, k;
+    float n_workers;      // compress only
+    const int* tile_block;  // [T] basis of the first slice of every 16-slice tile (B > 1 only)
+    int run_tiles;        // tile schedule, see TileIter
+};
+
+// Largest b with offs[b] <= j (offs[0] = 0, offs[B] = S > j).
+__device__ __forceinline__ int find_block(const int64_t* offs, int B, int64_t j)
+{
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (offs[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ float bf16_to_f32(unsigned int hi16)
+{
+    return __uint_as_float(hi16 << 16);
+}
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (NaN kept quiet).
+__device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
+{
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Orders this wave's LDS traffic for the compiler: what one lane wrote is read by another
+// lane of the same wave afterwards.  The hardware executes a wave's LDS instructions in
+// order, so no s_barrier is needed; this only stops the compiler from moving LDS accesses
+// across the exchange point.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T>
+__device__ __forceinline__ T stream_load(const T* p)
+{
+#if GVQ_NONTEMPORAL
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void stream_store(T* p, T v)
+{
+#if GVQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// Which tiles a wave works on: runs of R consecutive 16-slice tiles, run r = w, w+W, w+2W, ...
+// for wave w of W.  R = 1 interleaves single tiles, so that at any moment the whole chip
+// reads one compact window of memory (what HBM likes best); a longer run keeps a wave inside
+// one basis for longer when there are many bases; R = ceil(T/W) gives every wave one
+// contiguous chunk.
+struct TileIter {
+    int64_t t, run, run_end, T, W;
+    int R;
+    __device__ __forceinline__ bool init(int64_t T_, int R_)
+    {
+        T = T_; R = R_;
+        W = (int64_t)gridDim.x * WAVES_PER_WG;
+        run = (int64_t)blockIdx.x * WAVES_PER_WG + (threadIdx.x >> 6);
+        t = run * R;
+        run_end = t + R < T ? t + R : T;
+        return t < T;
+    }
+    __device__ __forceinline__ bool advance()
+    {
+        if (++t < run_end) return true;
+        run += W;
+        t = run * R;
+        run_end = t + R < T ? t + R : T;
+        return t < T;
+    }
+};
+
+__device__ __forceinline__ int block_of_tile(const CodecArgs& a, int64_t t)
+{
+    return a.B > 1 ? a.tile_block[t] : 0;
+}
+
+// XOR swizzle of the 128-bit LDS slots of a 16-row tile with D/4 slots per row: slot
+// s*CPS + (c ^ swz(s)) keeps 8 consecutive lanes on 8 distinct 128-bit bank groups both for
+// row-major (memory order) and for column-major (one row per lane) accesses.
+template <int D>
+__device__ __forceinline__ int swz(int s)
+{
+    return (D >= 32) ? (s & 7) : ((s >> 1) & 3);
+}
+

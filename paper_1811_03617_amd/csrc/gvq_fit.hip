@@ -504,6 +504,36 @@ __global__ void eigen_kernel(EigArgs a)
     if (tid == 0) a.sweeps[b] = sweeps_used;
 }
 
+// Section 3, Eq. (5): smallest k with (eig[0] + .. + eig[k-1]) / sum(eig) >= 1 - lambda; one
+// thread per basis, partial sums from the largest eigenvalue down, in double.
+__global__ void select_k_kernel(const double* eig, int d, int B, double lambda, int* k_out)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const double* e = eig + (size_t)b * d;
+    double total = 0.0;
+    for (int i = 0; i < d; ++i) total += e[i];
+    int k = d;
+    if (!(total > 0.0)) {
+        k = 1;
+    } else {
+        double cum = 0.0;
+        for (int i = 1; i <= d; ++i) {
+            cum += e[i - 1];
+            if (cum / total >= 1.0 - lambda) { k = i; break; }
+        }
+    }
+    k_out[b] = k;
+}
+
+int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st)
+{
+    hipLaunchKernelGGL(select_k_kernel, dim3((h->B + 63) / 64), dim3(64), 0, st, h->d_eig, h->d, h->B, lambda,
+                       h->d_ksel);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
 // ======================================================================================
 template <int TB>
 static void launch_moments(const gvq_basis* h, const MomArgs& a, hipStream_t st)

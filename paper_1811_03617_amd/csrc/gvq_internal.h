@@ -28,6 +28,10 @@ struct gvq_basis {
     int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
     int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
+    int* d_ksel = nullptr;      // [B] result of the last gvq_select_k
+    float* d_loss_slice = nullptr;  // [S] per-slice squared residual of the last gvq_local_loss
+    double* d_loss_part = nullptr;  // [B][loss_groups] partial sums of those
+    int loss_groups = 1;
     int P = 0;                  // moment partials per basis
     int fit_L = 0;              // gradients of the last fit
     bool fitted = false;        // basis usable (fit or import)
@@ -60,6 +64,9 @@ int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, f
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt,
                           hipStream_t st);
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
+int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
+                          hipStream_t st);
+int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st);
 // Refresh the operand-order copies of U after d_U changed (no-op for non-MFMA shapes).
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st);
 bool gvq_mfma_shape(int d, int k);

@@ -49,12 +49,15 @@ def lib():
         L.gvq_basis_export.argtypes = [vp, vp, vp, vp]
         L.gvq_basis_export_cov.argtypes = [vp, vp, vp]
         L.gvq_basis_import.argtypes = [vp, vp, vp]
+        L.gvq_local_loss.argtypes = [vp, vp, i32, vp, vp]
+        L.gvq_select_k.argtypes = [vp, C.c_double, C.POINTER(i32), vp]
         L.gvq_strerror.argtypes = [i32]
         L.gvq_strerror.restype = C.c_char_p
         L.gvq_set_option.argtypes = [i32, i32]
         for name in ("gvq_basis_create", "gvq_basis_destroy", "gvq_fit_basis", "gvq_fit_status",
                      "gvq_compress", "gvq_aggregate", "gvq_decompress", "gvq_basis_export",
-                     "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option"):
+                     "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option", "gvq_local_loss",
+                     "gvq_select_k"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -136,6 +139,16 @@ def gvq_decompress(h, comp_sum, grad_out, out_dtype=F32, stream=None):
            "gvq_decompress")
 
 
+def gvq_local_loss(h, grad, n_workers, loss_out, stream=None):
+    _check(lib().gvq_local_loss(h, _ptr(grad), int(n_workers), _ptr(loss_out), _stream(stream)), "gvq_local_loss")
+
+
+def gvq_select_k(h, lam, n_bases, stream=None):
+    out = (C.c_int * n_bases)()
+    _check(lib().gvq_select_k(h, float(lam), out, _stream(stream)), "gvq_select_k")
+    return list(out)
+
+
 def gvq_set_option(option, value):
     _check(lib().gvq_set_option(int(option), int(value)), "gvq_set_option")
 
@@ -181,6 +194,12 @@ class Basis:
         if out_dtype is None:
             out_dtype = self.dtype
         gvq_decompress(self._h, comp_sum, grad_out, BF16 if out_dtype == "bf16" else F32, stream)
+
+    def local_loss(self, grad, n_workers, loss_out, stream=None):
+        gvq_local_loss(self._h, grad, n_workers, loss_out, stream)
+
+    def select_k(self, lam, stream=None):
+        return gvq_select_k(self._h, lam, self.B, stream)
 
     def export(self):
         U = np.empty((self.B, self.d, self.k), dtype=np.float32)
