@@ -56,7 +56,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
@@ -126,6 +126,10 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             const size_t kp = k <= 16 ? 16 : 32;
             TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * d * kp));
             TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * d * kp));
+            if (gvq_bf16_pipe_shape(h)) {
+                TRY(hipMalloc((void**)&h->d_Upb, sizeof(unsigned short) * B * d * kp * 3));
+                TRY(hipMalloc((void**)&h->d_Umu, sizeof(float) * B * kp));
+            }
         }
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));

@@ -278,6 +278,155 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
     }
 }
 
+// --------------------------------------------------------------------------------------
+// compress for bf16-stored gradients on the bf16 matrix pipe, D in {32,64,128}.
+//
+// A bf16 input needs no conversion at all: 8 consecutive elements of a slice are exactly one
+// B operand of v_mfma_f32_16x16x32_bf16.  U is fp32; it is split once per basis into three
+// bf16 terms u1 + u2 + u3 (each the bf16 rounding of what the previous terms left over, which
+// reproduces all 24 mantissa bits), so three MFMAs give the fp32-exact products and the
+// accumulation stays fp32 -- a sixth of the fp32 pipe's cycles, no VALU conversion work, half
+// the LDS traffic.  Eq. (2)'s centring cannot be applied to the bf16 operand, so it becomes
+// the accumulator's start value: y = U^T x - U^T mu / N (algebraically the same; it costs
+// digits only when |mu|/N exceeds the spread of x by ~1e3, far beyond what bf16 storage
+// itself resolves).
+// Tile staging is the same as in the fp32 kernel (memory-order 128-bit loads, swizzled LDS,
+// lane = slice on the way back); MFMA step st of lane (n, kk) contracts elements
+// 8(4 st + kk) .. +7.
+// --------------------------------------------------------------------------------------
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+
+template <int D, int NT>
+__global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs a)
+{
+    constexpr int C8 = D / 8;                        // 128-bit chunks (8 bf16) per slice
+    constexpr int TILE_LOADS = TILE_SLICES * C8;
+    constexpr int NL = (TILE_LOADS + 63) / 64;
+    constexpr int NST = D / 32;                      // MFMA steps per tile
+    constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
+
+    __shared__ u4 lds_all[WAVES_PER_WG][TILE_SLICES * C8];
+    const int lane = threadIdx.x & 63;
+    u4* lds = lds_all[threadIdx.x >> 6];
+    const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
+    TileIter it;
+    if (!it.init(T, a.run_tiles)) return;
+    const int n_ = lane & 15, kk = lane >> 4;
+    const bool loads = lane < TILE_LOADS;            // false only for the upper lanes at D = 32
+
+    int cur_b = block_of_tile(a, it.t);
+    int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
+    u4 ua[NST][3][NT];   // bf16 x 8: part p of U[8(4 st + kk) + j][16 nt + n_], j = 0..7
+    f4 bias[NT];         // (U^T mu)[16 nt + 4 kk + r] / N
+    auto load_basis = [&](int b) {
+        const u4* Up = (const u4*)a.Upack + (size_t)b * (NST * 3 * NT * 64) + lane;
+#pragma unroll
+        for (int st = 0; st < NST; ++st)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) ua[st][p][nt] = Up[((st * 3 + p) * NT + nt) * 64];
+        const f4* um = (const f4*)(a.Umu + (size_t)b * 16 * NT) + kk;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bias[nt] = um[4 * nt] / a.n_workers;
+    };
+    load_basis(cur_b);
+
+    u4 regs[NL];
+    auto load_tile = [&](int64_t t) {
+        const int64_t base = t * TILE_ELEMS;
+        const unsigned short* p = (const unsigned short*)a.in;
+        if (base + TILE_ELEMS <= a.M) {
+#pragma unroll
+            for (int r = 0; r < NL; ++r)
+                if (NL * 64 == TILE_LOADS || loads) regs[r] = stream_load((const u4*)(p + base + (int64_t)(r * 64 + lane) * 8));
+            return;
+        }
+#pragma unroll
+        for (int r = 0; r < NL; ++r) {
+            const int g = r * 64 + lane;
+            const int64_t e0 = base + (int64_t)g * 8;
+            u4 v = {0u, 0u, 0u, 0u};
+            if (g < TILE_LOADS && e0 < a.M) {
+                if (e0 + 8 <= a.M) {
+                    v = *(const u4*)(p + e0);
+                } else {
+                    unsigned int h[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) h[i] = e0 + i < a.M ? p[e0 + i] : 0u;
+                    v = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+                }
+            }
+            regs[r] = v;
+        }
+    };
+
+    load_tile(it.t);
+    for (bool more = true; more;) {
+        const int64_t t = it.t;
+        const int64_t s0 = t * TILE_SLICES;
+        const int64_t s1 = s0 + TILE_SLICES < a.S ? s0 + TILE_SLICES : a.S;
+        if (s0 >= blk_end || s0 < blk_begin) {
+            cur_b = block_of_tile(a, t);
+            blk_begin = a.offs[cur_b];
+            blk_end = a.offs[cur_b + 1];
+            load_basis(cur_b);
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < NL; ++r) {
+            const int g = r * 64 + lane;
+            if (NL * 64 == TILE_LOADS || loads) {
+                const int s = g / C8, c = g % C8;
+                lds[s * C8 + (c ^ swz<D / 2>(s))] = regs[r];
+            }
+        }
+        wave_lds_sync();
+        more = it.advance();
+        if (more) load_tile(it.t);
+
+        u4 xb[NST];
+#pragma unroll
+        for (int st = 0; st < NST; ++st) xb[st] = lds[n_ * C8 + ((4 * st + kk) ^ swz<D / 2>(n_))];
+        __builtin_amdgcn_s_setprio(3);
+        for (;;) {
+            f4 acc[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[nt] = -bias[nt];
+#pragma unroll
+            for (int st = 0; st < NST; ++st)
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf8, ua[st][p][nt]), __builtin_bit_cast(bf8, xb[st]), acc[nt], 0, 0, 0);
+            const int64_t j = s0 + n_;
+            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
+            if (j >= lo && j < hi) {
+                float* o = (float*)a.out + j * a.k;
+                if ((a.k & 3) == 0) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        if (16 * nt + 4 * kk < a.k) stream_store((f4*)(o + 16 * nt + 4 * kk), acc[nt]);
+                } else {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (16 * nt + 4 * kk + r < a.k) o[16 * nt + 4 * kk + r] = acc[nt][r];
+                }
+            }
+            if (blk_end >= s1) break;
+            cur_b += 1;               // the tile continues into the next basis
+            blk_begin = blk_end;
+            blk_end = a.offs[cur_b + 1];
+            load_basis(cur_b);
+        }
+        __builtin_amdgcn_s_setprio(0);
+    }
+}
+
 // compress, any d <= 128 and k <= d: one thread per output number.  Correct, not fast.
 template <bool BF16>
 __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
@@ -557,6 +706,41 @@ __global__ void pack_basis_kernel(const float* U, float* Upc, float* Upd, int d,
     }
 }
 
+// For the bf16 compress kernel (d in {32,64,128}):
+//   Upb[b][st][p][nt][lane][j] (bf16) = term p of U[8(4 st + kk) + j][16 nt + n], U = u1 + u2 + u3 with
+//       u1 = bf16(U), u2 = bf16(U - u1), u3 = bf16(U - u1 - u2)   (round to nearest even; the
+//       differences are exact in fp32), zero past column k;
+//   Umu[b][c] = sum_e U[e][c] mu[e]  (float64 sum, stored as float), c < 16 NT, zero past k.
+__global__ void pack_basis_bf16_kernel(const float* U, const float* mu, unsigned short* Upb, float* Umu,
+                                       int d, int k, int NT)
+{
+    const int b = blockIdx.x;
+    const float* Ub = U + (size_t)b * d * k;
+    const float* mub = mu + (size_t)b * d;
+    const int NST = d / 32;
+    const int per = NST * 3 * NT * 64 * 8;   // bf16 values per basis
+    for (int i = threadIdx.x; i < per; i += blockDim.x) {
+        const int j = i & 7, lane = (i >> 3) & 63, n = lane & 15, kk = lane >> 4, hi = i >> 9;
+        const int nt = hi % NT, p = (hi / NT) % 3, st = hi / (3 * NT);
+        const int e = 8 * (4 * st + kk) + j, c = 16 * nt + n;
+        unsigned int out = 0u;
+        if (c < k) {
+            float rest = Ub[e * k + c];
+            for (int t = 0; t <= p; ++t) {
+                out = f32_to_bf16_rne(rest);
+                rest -= bf16_to_f32(out);
+            }
+        }
+        Upb[(size_t)b * per + i] = (unsigned short)out;
+    }
+    for (int c = threadIdx.x; c < 16 * NT; c += blockDim.x) {
+        double acc = 0.0;
+        if (c < k)
+            for (int e = 0; e < d; ++e) acc += (double)Ub[e * k + c] * (double)mub[e];
+        Umu[(size_t)b * 16 * NT + c] = (float)acc;
+    }
+}
+
 // ======================================================================================
 // host side
 // ======================================================================================
@@ -565,12 +749,23 @@ bool gvq_mfma_shape(int d, int k)
     return k <= 32 && (d == 16 || d == 32 || d == 64 || d == 128);
 }
 
+// bf16-stored gradients whose slices fill whole 32-element MFMA steps take the bf16 pipe
+bool gvq_bf16_pipe_shape(const gvq_basis* h)
+{
+    return h->dtype == GVQ_BF16 && gvq_mfma_shape(h->d, h->k) && h->d >= 32;
+}
+
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st)
 {
     if (!gvq_mfma_shape(h->d, h->k)) return GVQ_OK;
     hipLaunchKernelGGL(pack_basis_kernel, dim3(h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd,
                        h->d, h->k, h->k <= 16 ? 1 : 2);
     GVQ_HIP(hipGetLastError());
+    if (gvq_bf16_pipe_shape(h)) {
+        hipLaunchKernelGGL(pack_basis_bf16_kernel, dim3(h->B), dim3(256), 0, st, h->d_U, h->d_mu, h->d_Upb,
+                           h->d_Umu, h->d, h->k, h->k <= 16 ? 1 : 2);
+        GVQ_HIP(hipGetLastError());
+    }
     return GVQ_OK;
 }
 
@@ -582,6 +777,8 @@ static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_
     a.n_workers = (float)n_workers;
     a.tile_block = h->d_tile_block;
     a.run_tiles = 1;
+    a.Upack2 = nullptr;
+    a.Umu = nullptr;
     return a;
 }
 
@@ -641,8 +838,36 @@ static int launch_compress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t
     return h->k <= 16 ? launch_compress_t<D, 1, BF16>(h, a, st) : launch_compress_t<D, 2, BF16>(h, a, st);
 }
 
+template <int D, int NT>
+static int launch_compress_bf16_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    auto kern = compress_bf16_kernel<D, NT>;
+    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    int grid = streaming_grid(h, kern, tiles);
+    CodecArgs b = a;
+    b.run_tiles = run_length(h, tiles, grid);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+template <int D>
+static int launch_compress_bf16_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    return h->k <= 16 ? launch_compress_bf16_t<D, 1>(h, a, st) : launch_compress_bf16_t<D, 2>(h, a, st);
+}
+
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out, hipStream_t st)
 {
+    if (gvq_bf16_pipe_shape(h)) {
+        CodecArgs a = make_args(h, grad, out, n_workers, (const float*)h->d_Upb);
+        a.Umu = h->d_Umu;
+        switch (h->d) {
+        case 32: return launch_compress_bf16_d<32>(h, a, st);
+        case 64: return launch_compress_bf16_d<64>(h, a, st);
+        default: return launch_compress_bf16_d<128>(h, a, st);
+        }
+    }
     CodecArgs a = make_args(h, grad, out, n_workers, h->d_Upc);
     const bool bf = h->dtype == GVQ_BF16;
     if (gvq_mfma_shape(h->d, h->k)) {

@@ -19,6 +19,7 @@ struct CodecArgs {
     const float* U;       // [B][d][k]
     const f4* Upack;      // MFMA-operand order copy of U for this kernel, see pack_basis_kernel
     const f4* Upack2;     // local-loss kernel only: the decompress-order copy
+    const float* Umu;     // bf16 compress kernel only: [B][16 NT] U^T mu
     const float* mu;      // [B][d]
     const int64_t* offs;  // [B+1] slice offsets of the bases
     int64_t M, S;

@@ -20,6 +20,8 @@ struct gvq_basis {
     float* d_mu = nullptr;      // [B][d]
     float* d_Upc = nullptr;     // [B][d][KP] U in compress-MFMA operand order (MFMA shapes only)
     float* d_Upd = nullptr;     // [B][d][KP] U in decompress-MFMA operand order
+    unsigned short* d_Upb = nullptr;  // [B][d/32][3][NT][64][8] bf16 three-term split of U (bf16 gradients)
+    float* d_Umu = nullptr;     // [B][KP] U^T mu (bf16 gradients)
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
     double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
@@ -70,6 +72,7 @@ int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st);
 // Refresh the operand-order copies of U after d_U changed (no-op for non-MFMA shapes).
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st);
 bool gvq_mfma_shape(int d, int k);
+bool gvq_bf16_pipe_shape(const gvq_basis* h);
 bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
