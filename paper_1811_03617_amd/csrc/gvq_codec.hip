@@ -594,10 +594,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
                     const f4 v1 = lds[s * CPS + ((2 * c + 1) ^ swz<D>(s))];
                     unsigned short* o = (unsigned short*)a.out;
                     if (whole || (s0 + s >= lo && s0 + s < hi && e0 + 8 <= a.M)) {
-                        u4 pk = {f32_to_bf16_rne(v0[0]) | (f32_to_bf16_rne(v0[1]) << 16),
-                                 f32_to_bf16_rne(v0[2]) | (f32_to_bf16_rne(v0[3]) << 16),
-                                 f32_to_bf16_rne(v1[0]) | (f32_to_bf16_rne(v1[1]) << 16),
-                                 f32_to_bf16_rne(v1[2]) | (f32_to_bf16_rne(v1[3]) << 16)};
+                        u4 pk = {pack_bf16x2(v0[0], v0[1]), pack_bf16x2(v0[2], v0[3]),
+                                 pack_bf16x2(v1[0], v1[1]), pack_bf16x2(v1[2], v1[3])};
                         stream_store((u4*)(o + e0), pk);
                     } else if (s0 + s >= lo && s0 + s < hi) {
 #pragma unroll

@@ -53,6 +53,15 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> packed bf16 (round to nearest even) in one v_cvt_pk_bf16_f32; low half = a.
+typedef __bf16 gvq_bf2 __attribute__((ext_vector_type(2)));
+typedef float gvq_f2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned int pack_bf16x2(float a, float b)
+{
+    const gvq_f2 v = {a, b};
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, gvq_bf2));
+}
+
 // Orders this wave's LDS traffic for the compiler: what one lane wrote is read by another
 // lane of the same wave afterwards.  The hardware executes a wave's LDS instructions in
 // order, so no s_barrier is needed; this only stops the compiler from moving LDS accesses
