@@ -2,7 +2,7 @@
 import numpy as np
 import scipy.linalg
 
-REL_TOL = 1e-4      # spec tolerance on the codec, fp32 vs float64 oracle
+REL_TOL = 1e-4      # tolerance on the codec: fp32 kernels vs the float64 oracle, relative
 ANGLE_TOL = 1e-3    # radians, largest principal angle between fitted bases
 
 

@@ -17,7 +17,7 @@ def _declared():
     return sorted(set(re.findall(r"\b(gvq_[a-z_]+)\s*\(", text)))
 
 
-def test_header_declares_the_four_north_star_calls():
+def test_header_declares_the_four_codec_calls():
     names = _declared()
     for n in ("gvq_fit_basis", "gvq_compress", "gvq_aggregate", "gvq_decompress"):
         assert n in names
