@@ -124,6 +124,24 @@ int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out,
                    gvq_dtype_t out_dtype, void* stream);
 
 /*
+ * Building blocks of Algorithm 1 (compression overlapped with the ring all-reduce): the same
+ * operations restricted to the slices [first_slice, first_slice + n_slices), one ring segment.
+ * All buffers are the full-size ones; only the segment's rows (elements) are read and written,
+ * at their usual positions, so a segment of the compressed vector is the contiguous byte range
+ * comp + first_slice*k.  0 <= first_slice, first_slice + n_slices <= S.
+ *
+ * gvq_compress_segment: comp_out[j][:] = Q(x_j) (Eq. 2) + comp_in[j][:] for j in the segment;
+ * comp_in (device, may be NULL = nothing to add, may equal comp_out) is the partial sum
+ * received from the predecessor -- one fused step of Algorithm 1's compression round, which
+ * saves a separate pass over the compressed data.
+ * gvq_decompress_segment: Eq. (4) on the segment's slices (decompression round).
+ */
+int gvq_compress_segment(const gvq_basis_t* h, const void* grad, int n_workers, int64_t first_slice,
+                         int64_t n_slices, const float* comp_in, float* comp_out, void* stream);
+int gvq_decompress_segment(const gvq_basis_t* h, const float* comp_sum, int64_t first_slice,
+                           int64_t n_slices, void* grad_out, gvq_dtype_t out_dtype, void* stream);
+
+/*
  * Section 3, Eq. (6): the local compression loss of one worker's gradient,
  *     loss_out[b] = sum over the slices of basis b of || x - (U_b y + mu_b/N) ||^2,
  *     y = U_b^T (x - mu_b/N)   (Eq. 2),

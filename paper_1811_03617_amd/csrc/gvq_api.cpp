@@ -222,7 +222,18 @@ int gvq_compress(const gvq_basis_t* h, const void* grad, int n_workers, float* c
     if (!h || !grad || !comp_out || n_workers < 1) return GVQ_EINVAL;
     if (!aligned16(grad) || !aligned16(comp_out)) return GVQ_EALIGN;
     if (!h->fitted) return GVQ_ENOTFIT;
-    return gvq_launch_compress(h, grad, n_workers, comp_out, (hipStream_t)stream);
+    return gvq_launch_compress(h, grad, n_workers, 0, h->S, nullptr, comp_out, (hipStream_t)stream);
+}
+
+int gvq_compress_segment(const gvq_basis_t* h, const void* grad, int n_workers, int64_t first_slice,
+                         int64_t n_slices, const float* comp_in, float* comp_out, void* stream)
+{
+    if (!h || !grad || !comp_out || n_workers < 1) return GVQ_EINVAL;
+    if (first_slice < 0 || n_slices < 0 || first_slice > h->S || n_slices > h->S - first_slice) return GVQ_EINVAL;
+    if (!aligned16(grad) || !aligned16(comp_out) || (comp_in && !aligned16(comp_in))) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    if (n_slices == 0) return GVQ_OK;
+    return gvq_launch_compress(h, grad, n_workers, first_slice, n_slices, comp_in, comp_out, (hipStream_t)stream);
 }
 
 int gvq_aggregate(const gvq_basis_t* h, const float* const* comps, int N, float* comp_sum, void* stream)
@@ -244,7 +255,19 @@ int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out, 
     if (out_dtype != GVQ_F32 && out_dtype != GVQ_BF16) return GVQ_EINVAL;
     if (!aligned16(comp_sum) || !aligned16(grad_out)) return GVQ_EALIGN;
     if (!h->fitted) return GVQ_ENOTFIT;
-    return gvq_launch_decompress(h, comp_sum, grad_out, out_dtype, (hipStream_t)stream);
+    return gvq_launch_decompress(h, comp_sum, 0, h->S, grad_out, out_dtype, (hipStream_t)stream);
+}
+
+int gvq_decompress_segment(const gvq_basis_t* h, const float* comp_sum, int64_t first_slice, int64_t n_slices,
+                           void* grad_out, gvq_dtype_t out_dtype, void* stream)
+{
+    if (!h || !comp_sum || !grad_out) return GVQ_EINVAL;
+    if (out_dtype != GVQ_F32 && out_dtype != GVQ_BF16) return GVQ_EINVAL;
+    if (first_slice < 0 || n_slices < 0 || first_slice > h->S || n_slices > h->S - first_slice) return GVQ_EINVAL;
+    if (!aligned16(comp_sum) || !aligned16(grad_out)) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    if (n_slices == 0) return GVQ_OK;
+    return gvq_launch_decompress(h, comp_sum, first_slice, n_slices, grad_out, out_dtype, (hipStream_t)stream);
 }
 
 int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out, void* stream)

@@ -44,9 +44,8 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
     f4* lds = lds_all[threadIdx.x >> 6];
     f4* ldso = ldso_all[threadIdx.x >> 6];
 
-    const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
     TileIter it;
-    if (!it.init(T, a.run_tiles)) return;
+    if (!init_tiles(it, a)) return;
 
     const int n_ = lane & 15, kk = lane >> 4;
     // result tile in memory order: 16 slices x k floats, contiguous; this lane's 128-bit pieces
@@ -166,10 +165,13 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
         if constexpr ((VAR & 2) != 0) __builtin_amdgcn_s_setprio(3);
 
         for (;;) {
+            int64_t lo, hi;
+            row_range(a, s0, s1, blk_begin, blk_end, lo, hi);
             f4 x[NQ];
 #pragma unroll
             for (int q = 0; q < NQ; ++q) x[q] = lds[n_ * CPS + ((4 * q + kk) ^ swz<D>(n_))];
-            f4 acc[NT];
+            f4 acc[NT], prev[NT];
+            if constexpr ((VAR & 4) != 0) load_acc_in<NT>(a, s0 + n_, kk, s0 + n_ >= lo && s0 + n_ < hi, prev);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -179,8 +181,11 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[q][j], acc[nt], 0, 0, 0);
+            if constexpr ((VAR & 4) != 0) {   // ring step: add the predecessor's partial sum
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] += prev[nt];
+            }
             // lane holds comps 16*nt + 4*kk + r of slice s0 + n_
-            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
             if constexpr (LOSS) {
                 // Eq. (6): reconstruct U y from the accumulators (they already sit in the
                 // B-operand order of the second product) and compare with the parked x - mu/N;
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
 // --------------------------------------------------------------------------------------
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
-template <int D, int NT>
+template <int D, int NT, bool ACC>
 __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs a)
 {
     constexpr int C8 = D / 8;                        // 128-bit chunks (8 bf16) per slice
@@ -308,9 +313,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
     __shared__ u4 lds_all[WAVES_PER_WG][TILE_SLICES * C8];
     const int lane = threadIdx.x & 63;
     u4* lds = lds_all[threadIdx.x >> 6];
-    const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
     TileIter it;
-    if (!it.init(T, a.run_tiles)) return;
+    if (!init_tiles(it, a)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const bool loads = lane < TILE_LOADS;            // false only for the upper lanes at D = 32
 
@@ -390,7 +394,10 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
         for (int st = 0; st < NST; ++st) xb[st] = lds[n_ * C8 + ((4 * st + kk) ^ swz<D / 2>(n_))];
         __builtin_amdgcn_s_setprio(3);
         for (;;) {
-            f4 acc[NT];
+            int64_t lo, hi;
+            row_range(a, s0, s1, blk_begin, blk_end, lo, hi);
+            f4 acc[NT], prev[NT];
+            if constexpr (ACC) load_acc_in<NT>(a, s0 + n_, kk, s0 + n_ >= lo && s0 + n_ < hi, prev);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[nt] = -bias[nt];
 #pragma unroll
@@ -401,8 +408,11 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf8, ua[st][p][nt]), __builtin_bit_cast(bf8, xb[st]), acc[nt], 0, 0, 0);
+            if constexpr (ACC) {   // ring step: add the predecessor's partial sum
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] += prev[nt];
+            }
             const int64_t j = s0 + n_;
-            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
             if (j >= lo && j < hi) {
                 float* o = (float*)a.out + j * a.k;
                 if ((a.k & 3) == 0) {
@@ -431,8 +441,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
 template <bool BF16>
 __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
 {
-    const int64_t total = a.S * a.k;
-    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+    const int64_t first = a.seg_begin * a.k, total = a.seg_end * a.k;
+    for (int64_t o = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
          o += (int64_t)gridDim.x * blockDim.x) {
         const int64_t j = o / a.k;
         const int c = (int)(o - j * a.k);
@@ -447,6 +457,7 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
                 x = BF16 ? bf16_to_f32(((const unsigned short*)a.in)[idx]) : ((const float*)a.in)[idx];
             acc = fmaf(Ub[e * a.k + c], x - mub[e] / a.n_workers, acc);
         }
+        if (a.acc_in) acc += a.acc_in[o];
         ((float*)a.out)[o] = acc;
     }
 }
@@ -478,9 +489,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
     const int lane = threadIdx.x & 63;
     f4* lds = lds_all[threadIdx.x >> 6];
     f4* ldsi = ldsi_all[threadIdx.x >> 6];
-    const int64_t T = (a.S + TILE_SLICES - 1) / TILE_SLICES;
     TileIter it;
-    if (!it.init(T, a.run_tiles)) return;
+    if (!init_tiles(it, a)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const float* Y = (const float*)a.in;
     const bool vec = (a.k & 3) == 0;
@@ -581,7 +591,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
             }
             wave_lds_sync();
             // write the tile out in memory order
-            const int64_t lo = s0 > blk_begin ? s0 : blk_begin, hi = s1 < blk_end ? s1 : blk_end;
+            int64_t lo, hi;
+            row_range(a, s0, s1, blk_begin, blk_end, lo, hi);
             const bool whole = lo == s0 && hi == s0 + TILE_SLICES && (s0 + TILE_SLICES) * (int64_t)D <= a.M;
 #pragma unroll
             for (int r = 0; r < NS; ++r) {
@@ -631,7 +642,8 @@ template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void decompress_generic_kernel(CodecArgs a)
 {
     const float* Y = (const float*)a.in;
-    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < a.M;
+    const int64_t first = a.seg_begin * a.d, last = a.seg_end * a.d < a.M ? a.seg_end * a.d : a.M;
+    for (int64_t o = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < last;
          o += (int64_t)gridDim.x * blockDim.x) {
         const int64_t j = o / a.d;
         const int e = (int)(o - j * a.d);
@@ -777,6 +789,9 @@ static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_
     a.run_tiles = 1;
     a.Upack2 = nullptr;
     a.Umu = nullptr;
+    a.acc_in = nullptr;
+    a.seg_begin = 0;
+    a.seg_end = h->S;
     return a;
 }
 
@@ -812,7 +827,7 @@ template <int D, int NT, bool BF16, int VAR>
 static int launch_compress_v(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false>;
-    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
@@ -826,7 +841,9 @@ static int launch_compress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t
 {
     // VAR bit 0: results leave through LDS as full-width stores (pays at k > 16, where a slice's
     // results would otherwise leave in two half-line pieces); bit 1: raised wave priority
-    // while a wave feeds the MFMA pipe.  Both measured: +1..3 %.
+    // while a wave feeds the MFMA pipe.  Both measured: +1..3 %.  Bit 2: fused ring step
+    // (adds acc_in); a separate instantiation so that the plain kernel does not carry its registers.
+    if (a.acc_in) return launch_compress_v<D, NT, BF16, (NT == 2 ? 7 : 6)>(h, a, st);
     return launch_compress_v<D, NT, BF16, (NT == 2 ? 3 : 2)>(h, a, st);
 }
 
@@ -836,11 +853,11 @@ static int launch_compress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t
     return h->k <= 16 ? launch_compress_t<D, 1, BF16>(h, a, st) : launch_compress_t<D, 2, BF16>(h, a, st);
 }
 
-template <int D, int NT>
-static int launch_compress_bf16_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+template <int D, int NT, bool ACC>
+static int launch_compress_bf16_a(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = compress_bf16_kernel<D, NT>;
-    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    auto kern = compress_bf16_kernel<D, NT, ACC>;
+    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
@@ -849,17 +866,25 @@ static int launch_compress_bf16_t(const gvq_basis* h, const CodecArgs& a, hipStr
     return GVQ_OK;
 }
 
+template <int D, int NT>
+static int launch_compress_bf16_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    return a.acc_in ? launch_compress_bf16_a<D, NT, true>(h, a, st) : launch_compress_bf16_a<D, NT, false>(h, a, st);
+}
+
 template <int D>
 static int launch_compress_bf16_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     return h->k <= 16 ? launch_compress_bf16_t<D, 1>(h, a, st) : launch_compress_bf16_t<D, 2>(h, a, st);
 }
 
-int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out, hipStream_t st)
+int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
+                        int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
     if (gvq_bf16_pipe_shape(h)) {
         CodecArgs a = make_args(h, grad, out, n_workers, (const float*)h->d_Upb);
         a.Umu = h->d_Umu;
+        a.acc_in = comp_in; a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
         switch (h->d) {
         case 32: return launch_compress_bf16_d<32>(h, a, st);
         case 64: return launch_compress_bf16_d<64>(h, a, st);
@@ -867,6 +892,7 @@ int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, flo
         }
     }
     CodecArgs a = make_args(h, grad, out, n_workers, h->d_Upc);
+    a.acc_in = comp_in; a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
     const bool bf = h->dtype == GVQ_BF16;
     if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
@@ -877,7 +903,7 @@ int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, flo
         default: break;
         }
     }
-    int64_t total = h->S * h->k;
+    int64_t total = n_slices * h->k;
     int64_t want = (total + 255) / 256, cap = (int64_t)h->num_cu * 16;
     int grid = (int)(want < cap ? want : cap);
     if (bf)
@@ -892,7 +918,7 @@ template <int D, int NQ, bool OBF>
 static int launch_decompress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     auto kern = decompress_mfma_kernel<D, NQ, OBF>;
-    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
@@ -907,9 +933,11 @@ static int launch_decompress_d(const gvq_basis* h, const CodecArgs& a, hipStream
     return h->k <= 16 ? launch_decompress_t<D, 1, OBF>(h, a, st) : launch_decompress_t<D, 2, OBF>(h, a, st);
 }
 
-int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt, hipStream_t st)
+int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
+                          void* out, gvq_dtype_t odt, hipStream_t st)
 {
     CodecArgs a = make_args(h, comp, out, 1, h->d_Upd);
+    a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
     const bool bf = odt == GVQ_BF16;
     if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
@@ -920,7 +948,7 @@ int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_
         default: break;
         }
     }
-    int64_t want = (h->M + 255) / 256, cap = (int64_t)h->num_cu * 16;
+    int64_t want = (n_slices * h->d + 255) / 256, cap = (int64_t)h->num_cu * 16;
     int grid = (int)(want < cap ? want : cap);
     if (bf)
         hipLaunchKernelGGL(decompress_generic_kernel<true>, dim3(grid), dim3(256), 0, st, a);
@@ -1045,7 +1073,7 @@ template <int D, int NT, bool BF16>
 static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     auto kern = compress_mfma_kernel<D, NT, BF16, 0, true>;
-    int64_t tiles = (h->S + TILE_SLICES - 1) / TILE_SLICES;
+    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
     int grid = streaming_grid(h, kern, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);

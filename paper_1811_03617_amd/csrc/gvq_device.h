@@ -20,6 +20,8 @@ struct CodecArgs {
     const f4* Upack;      // MFMA-operand order copy of U for this kernel, see pack_basis_kernel
     const f4* Upack2;     // local-loss kernel only: the decompress-order copy
     const float* Umu;     // bf16 compress kernel only: [B][16 NT] U^T mu
+    const float* acc_in;  // compress only, may be null: [S][k] added to the result (ring step of Algorithm 1)
+    int64_t seg_begin, seg_end;  // only the slices [seg_begin, seg_end) are produced
     const float* mu;      // [B][d]
     const int64_t* offs;  // [B+1] slice offsets of the bases
     int64_t M, S;
@@ -98,26 +100,66 @@ __device__ __forceinline__ void stream_store(T* p, T v)
 // one basis for longer when there are many bases; R = ceil(T/W) gives every wave one
 // contiguous chunk.
 struct TileIter {
-    int64_t t, run, run_end, T, W;
+    int64_t t, run, run_end, T0, T1, W;
     int R;
-    __device__ __forceinline__ bool init(int64_t T_, int R_)
+    // tiles [T0, T1)
+    __device__ __forceinline__ bool init(int64_t T0_, int64_t T1_, int R_)
     {
-        T = T_; R = R_;
+        T0 = T0_; T1 = T1_; R = R_;
         W = (int64_t)gridDim.x * WAVES_PER_WG;
         run = (int64_t)blockIdx.x * WAVES_PER_WG + (threadIdx.x >> 6);
-        t = run * R;
-        run_end = t + R < T ? t + R : T;
-        return t < T;
+        t = T0 + run * R;
+        run_end = t + R < T1 ? t + R : T1;
+        return t < T1;
     }
     __device__ __forceinline__ bool advance()
     {
         if (++t < run_end) return true;
         run += W;
-        t = run * R;
-        run_end = t + R < T ? t + R : T;
-        return t < T;
+        t = T0 + run * R;
+        run_end = t + R < T1 ? t + R : T1;
+        return t < T1;
     }
 };
+
+// The 16-slice tiles that touch the requested slice range.
+__device__ __forceinline__ bool init_tiles(TileIter& it, const CodecArgs& a)
+{
+    return it.init(a.seg_begin / TILE_SLICES, (a.seg_end + TILE_SLICES - 1) / TILE_SLICES, a.run_tiles);
+}
+
+// Ring step of Algorithm 1: the partial sum that arrived from the predecessor, in the register
+// layout of a result tile (lane (n, kk) holds comps 16 nt + 4 kk + r of slice j); zero where
+// there is nothing to add.
+template <int NT>
+__device__ __forceinline__ void load_acc_in(const CodecArgs& a, int64_t j, int kk, bool row_ok, f4 (&v)[NT])
+{
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        v[nt] = f4{0.f, 0.f, 0.f, 0.f};
+        if (a.acc_in && row_ok) {
+            const int c0 = 16 * nt + 4 * kk;
+            const float* p = a.acc_in + j * a.k + c0;
+            if ((a.k & 3) == 0) {
+                if (c0 < a.k) v[nt] = *(const f4*)p;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (c0 + r < a.k) v[nt][r] = p[r];
+            }
+        }
+    }
+}
+
+// Rows of the tile [s0, s1) that belong to the current basis and to the requested range.
+__device__ __forceinline__ void row_range(const CodecArgs& a, int64_t s0, int64_t s1, int64_t blk_begin,
+                                          int64_t blk_end, int64_t& lo, int64_t& hi)
+{
+    lo = s0 > blk_begin ? s0 : blk_begin;
+    hi = s1 < blk_end ? s1 : blk_end;
+    if (lo < a.seg_begin) lo = a.seg_begin;
+    if (hi > a.seg_end) hi = a.seg_end;
+}
 
 __device__ __forceinline__ int block_of_tile(const CodecArgs& a, int64_t t)
 {

@@ -59,12 +59,12 @@ int gvq_opt_wg_per_cu();
 int gvq_opt_run_tiles();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
-int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, float* out,
-                        hipStream_t st);
+int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
+                        int64_t n_slices, const float* comp_in, float* out, hipStream_t st);
 int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, float* out,
                          hipStream_t st);
-int gvq_launch_decompress(const gvq_basis* h, const float* comp, void* out, gvq_dtype_t odt,
-                          hipStream_t st);
+int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
+                          void* out, gvq_dtype_t odt, hipStream_t st);
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
 int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
                           hipStream_t st);

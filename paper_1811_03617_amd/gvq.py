@@ -49,6 +49,8 @@ def lib():
         L.gvq_basis_export.argtypes = [vp, vp, vp, vp]
         L.gvq_basis_export_cov.argtypes = [vp, vp, vp]
         L.gvq_basis_import.argtypes = [vp, vp, vp]
+        L.gvq_compress_segment.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp]
+        L.gvq_decompress_segment.argtypes = [vp, vp, i64, i64, vp, i32, vp]
         L.gvq_local_loss.argtypes = [vp, vp, i32, vp, vp]
         L.gvq_select_k.argtypes = [vp, C.c_double, C.POINTER(i32), vp]
         L.gvq_strerror.argtypes = [i32]
@@ -57,7 +59,7 @@ def lib():
         for name in ("gvq_basis_create", "gvq_basis_destroy", "gvq_fit_basis", "gvq_fit_status",
                      "gvq_compress", "gvq_aggregate", "gvq_decompress", "gvq_basis_export",
                      "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option", "gvq_local_loss",
-                     "gvq_select_k"):
+                     "gvq_select_k", "gvq_compress_segment", "gvq_decompress_segment"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -139,6 +141,16 @@ def gvq_decompress(h, comp_sum, grad_out, out_dtype=F32, stream=None):
            "gvq_decompress")
 
 
+def gvq_compress_segment(h, grad, n_workers, first_slice, n_slices, comp_in, comp_out, stream=None):
+    _check(lib().gvq_compress_segment(h, _ptr(grad), int(n_workers), int(first_slice), int(n_slices),
+                                      _ptr(comp_in), _ptr(comp_out), _stream(stream)), "gvq_compress_segment")
+
+
+def gvq_decompress_segment(h, comp_sum, first_slice, n_slices, grad_out, out_dtype=F32, stream=None):
+    _check(lib().gvq_decompress_segment(h, _ptr(comp_sum), int(first_slice), int(n_slices), _ptr(grad_out),
+                                        int(out_dtype), _stream(stream)), "gvq_decompress_segment")
+
+
 def gvq_local_loss(h, grad, n_workers, loss_out, stream=None):
     _check(lib().gvq_local_loss(h, _ptr(grad), int(n_workers), _ptr(loss_out), _stream(stream)), "gvq_local_loss")
 
@@ -194,6 +206,15 @@ class Basis:
         if out_dtype is None:
             out_dtype = self.dtype
         gvq_decompress(self._h, comp_sum, grad_out, BF16 if out_dtype == "bf16" else F32, stream)
+
+    def compress_segment(self, grad, n_workers, first_slice, n_slices, comp_in, comp_out, stream=None):
+        gvq_compress_segment(self._h, grad, n_workers, first_slice, n_slices, comp_in, comp_out, stream)
+
+    def decompress_segment(self, comp_sum, first_slice, n_slices, grad_out, out_dtype=None, stream=None):
+        if out_dtype is None:
+            out_dtype = self.dtype
+        gvq_decompress_segment(self._h, comp_sum, first_slice, n_slices, grad_out,
+                               BF16 if out_dtype == "bf16" else F32, stream)
 
     def local_loss(self, grad, n_workers, loss_out, stream=None):
         gvq_local_loss(self._h, grad, n_workers, loss_out, stream)
