@@ -124,6 +124,20 @@ int gvq_decompress(const gvq_basis_t* h, const float* comp_sum, void* grad_out,
                    gvq_dtype_t out_dtype, void* stream);
 
 /*
+ * Section 2 (gradient packing, Fig. 2a): reorder the gradient of one convolution layer, stored
+ * [F][D][H][W] (filters, depth, height, width -- the usual weight layout), into the flat order
+ * the codec slices:  flat[((h*W + w)*D + d)*F + f] = grad[f][d][h][w], i.e. the F collocated
+ * gradients of the F filters are adjacent and the groups run along depth, then width, then
+ * height.  gvq_unflatten_conv is the inverse.  Both pointers are device memory of F*D*H*W
+ * elements of `dtype`, aligned to the element size, not overlapping.  No handle: a model's
+ * layers are flattened one call each into their places of the big gradient vector.
+ */
+int gvq_flatten_conv(const void* grad, void* flat, int F, int D, int H, int W, gvq_dtype_t dtype,
+                     void* stream);
+int gvq_unflatten_conv(const void* flat, void* grad, int F, int D, int H, int W, gvq_dtype_t dtype,
+                       void* stream);
+
+/*
  * Building blocks of Algorithm 1 (compression overlapped with the ring all-reduce): the same
  * operations restricted to the slices [first_slice, first_slice + n_slices), one ring segment.
  * All buffers are the full-size ones; only the segment's rows (elements) are read and written,

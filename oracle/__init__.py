@@ -240,3 +240,30 @@ def local_loss(grad, U, mu, n_workers, dtype="f32", offsets=None):
     lib().gvq_oracle_local_loss(g.ctypes.data, M, d, k, _DT[dtype], B, _optr(o), _dptr(U), _dptr(mu),
                                 int(n_workers), _dptr(out))
     return out
+
+
+def flatten_conv(grad):
+    """Section 2 / Fig. 2a: gradient of a convolution layer stored [F, D, H, W] -> the flat order
+    in which the F collocated gradients of the F filters are adjacent and the groups run along
+    depth, then width, then height.  Written as the index formula, one element at a time."""
+    g = np.asarray(grad)
+    F, D, H, W = g.shape
+    flat = np.empty(F * D * H * W, dtype=g.dtype)
+    for h in range(H):
+        for w in range(W):
+            for d in range(D):
+                base = ((h * W + w) * D + d) * F
+                flat[base:base + F] = g[:, d, h, w]
+    return flat
+
+
+def unflatten_conv(flat, F, D, H, W):
+    """Inverse of flatten_conv."""
+    flat = np.asarray(flat)
+    g = np.empty((F, D, H, W), dtype=flat.dtype)
+    for h in range(H):
+        for w in range(W):
+            for d in range(D):
+                base = ((h * W + w) * D + d) * F
+                g[:, d, h, w] = flat[base:base + F]
+    return g

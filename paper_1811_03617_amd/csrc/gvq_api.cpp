@@ -289,6 +289,27 @@ int gvq_select_k(const gvq_basis_t* h, double lambda, int* k_out, void* stream)
     return GVQ_OK;
 }
 
+static int layout_call(const void* src, void* dst, int F, int D, int H, int W, gvq_dtype_t dtype, bool flatten,
+                       void* stream)
+{
+    if (!src || !dst || src == dst || F < 1 || D < 1 || H < 1 || W < 1) return GVQ_EINVAL;
+    if (dtype != GVQ_F32 && dtype != GVQ_BF16) return GVQ_EINVAL;
+    if ((int64_t)H * W > (1 << 20) || (int64_t)F * D * H * W > ((int64_t)1 << 40)) return GVQ_EINVAL;
+    const uintptr_t mask = dtype == GVQ_BF16 ? 1u : 3u;
+    if (((uintptr_t)src & mask) || ((uintptr_t)dst & mask)) return GVQ_EALIGN;
+    return gvq_launch_layout(src, dst, F, D, H * W, dtype, flatten, (hipStream_t)stream);
+}
+
+int gvq_flatten_conv(const void* grad, void* flat, int F, int D, int H, int W, gvq_dtype_t dtype, void* stream)
+{
+    return layout_call(grad, flat, F, D, H, W, dtype, true, stream);
+}
+
+int gvq_unflatten_conv(const void* flat, void* grad, int F, int D, int H, int W, gvq_dtype_t dtype, void* stream)
+{
+    return layout_call(flat, grad, F, D, H, W, dtype, false, stream);
+}
+
 int gvq_basis_export(const gvq_basis_t* h, float* U, float* mu, double* eig)
 {
     if (!h) return GVQ_EINVAL;

@@ -51,6 +51,8 @@ def lib():
         L.gvq_basis_import.argtypes = [vp, vp, vp]
         L.gvq_compress_segment.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp]
         L.gvq_decompress_segment.argtypes = [vp, vp, i64, i64, vp, i32, vp]
+        L.gvq_flatten_conv.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        L.gvq_unflatten_conv.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         L.gvq_local_loss.argtypes = [vp, vp, i32, vp, vp]
         L.gvq_select_k.argtypes = [vp, C.c_double, C.POINTER(i32), vp]
         L.gvq_strerror.argtypes = [i32]
@@ -59,7 +61,8 @@ def lib():
         for name in ("gvq_basis_create", "gvq_basis_destroy", "gvq_fit_basis", "gvq_fit_status",
                      "gvq_compress", "gvq_aggregate", "gvq_decompress", "gvq_basis_export",
                      "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option", "gvq_local_loss",
-                     "gvq_select_k", "gvq_compress_segment", "gvq_decompress_segment"):
+                     "gvq_select_k", "gvq_compress_segment", "gvq_decompress_segment", "gvq_flatten_conv",
+                     "gvq_unflatten_conv"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -149,6 +152,15 @@ def gvq_compress_segment(h, grad, n_workers, first_slice, n_slices, comp_in, com
 def gvq_decompress_segment(h, comp_sum, first_slice, n_slices, grad_out, out_dtype=F32, stream=None):
     _check(lib().gvq_decompress_segment(h, _ptr(comp_sum), int(first_slice), int(n_slices), _ptr(grad_out),
                                         int(out_dtype), _stream(stream)), "gvq_decompress_segment")
+
+
+def gvq_flatten_conv(grad, flat, F, D, H, W, dtype=F32, stream=None):
+    _check(lib().gvq_flatten_conv(_ptr(grad), _ptr(flat), F, D, H, W, int(dtype), _stream(stream)), "gvq_flatten_conv")
+
+
+def gvq_unflatten_conv(flat, grad, F, D, H, W, dtype=F32, stream=None):
+    _check(lib().gvq_unflatten_conv(_ptr(flat), _ptr(grad), F, D, H, W, int(dtype), _stream(stream)),
+           "gvq_unflatten_conv")
 
 
 def gvq_local_loss(h, grad, n_workers, loss_out, stream=None):

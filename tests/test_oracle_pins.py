@@ -369,3 +369,19 @@ def test_local_loss_eq6_against_plain_numpy_and_identities():
     # k = d: nothing is lost
     Uf, muf, _ = oracle.fit(fitg, d, d, offsets=offs)
     assert np.all(oracle.local_loss(g, Uf, muf, N, offsets=offs) < 1e-24)
+
+
+# ---------------------------------------------------------------- gradient packing (Section 2, Fig. 2a)
+def test_flatten_conv_hand_example_and_structure():
+    # F = 2 filters, depth 2, 1 x 2 kernel; value encodes (f, d, h, w) as f d w digits
+    g = np.array([[[[000, 1]], [[10, 11]]], [[[100, 101]], [[110, 111]]]], dtype=np.float32)  # [F=2][D=2][H=1][W=2]
+    flat = oracle.flatten_conv(g)
+    # groups of F = 2 collocated gradients; groups run along depth first, then width
+    np.testing.assert_array_equal(flat, [0, 100, 10, 110, 1, 101, 11, 111])
+    rng = np.random.default_rng(0)
+    g = rng.standard_normal((5, 3, 2, 4)).astype(np.float32)
+    flat = oracle.flatten_conv(g)
+    np.testing.assert_array_equal(flat, np.transpose(g, (2, 3, 1, 0)).ravel())   # library re-statement
+    np.testing.assert_array_equal(oracle.unflatten_conv(flat, 5, 3, 2, 4), g)
+    # every run of F numbers holds one (d, h, w) position of all filters
+    np.testing.assert_array_equal(flat[7 * 5:8 * 5], g[:, 7 % 3, (7 // 3) // 4, (7 // 3) % 4])
