@@ -42,7 +42,7 @@ def lib():
         L.gvq_oracle_basis_from_cov.argtypes = [dp, i32, i32, dp, dp]
         L.gvq_oracle_basis_from_cov.restype = i32
         L.gvq_oracle_fit.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i32, i32,
-                                     C.POINTER(i64), dp, dp, dp, dp]
+                                     C.POINTER(i64), i32, dp, dp, dp, dp]
         L.gvq_oracle_fit.restype = i32
         L.gvq_oracle_compress.argtypes = [vp, i64, i32, i32, i32, i32, C.POINTER(i64), dp, dp,
                                           i32, i64, i64, dp]
@@ -145,8 +145,10 @@ def basis_from_cov(Cm, k):
     return U, eig, sweeps
 
 
-def fit(grads, d, k, dtype="f32", offsets=None, return_cov=False):
-    """Basis refresh: returns U [B,d,k], mu [B,d], eig [B,d] (and C [B,d,d])."""
+def fit(grads, d, k, dtype="f32", offsets=None, return_cov=False, first_slice_only=False):
+    """Basis refresh: returns U [B,d,k], mu [B,d], eig [B,d] (and C [B,d,d]).
+    first_slice_only: the samples of a basis are the L copies of its first slice only (the
+    paper's own sampling, Section 3 "compressor reuse") instead of all its slices."""
     if d > MAX_D:
         raise ValueError("d too large for the oracle")
     keep, arr, M = _grad_ptrs(grads, dtype)
@@ -156,7 +158,7 @@ def fit(grads, d, k, dtype="f32", offsets=None, return_cov=False):
     mu = np.empty((B, d), dtype=np.float64)
     eig = np.empty((B, d), dtype=np.float64)
     Cm = np.empty((B, d, d), dtype=np.float64) if return_cov else None
-    rc = lib().gvq_oracle_fit(arr, len(keep), M, d, k, _DT[dtype], B, _optr(o), _dptr(U),
+    rc = lib().gvq_oracle_fit(arr, len(keep), M, d, k, _DT[dtype], B, _optr(o), int(bool(first_slice_only)), _dptr(U),
                               _dptr(mu), _dptr(eig), _dptr(Cm) if return_cov else None)
     if rc != 0:
         raise RuntimeError(f"oracle fit failed (rc={rc})")

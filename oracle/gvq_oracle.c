@@ -305,13 +305,16 @@ int gvq_oracle_basis_from_cov(const double *C, int d, int k, double *U, double *
  * Returns 0, or -1 if an eigensolve did not converge.
  * ---------------------------------------------------------------------------------- */
 int gvq_oracle_fit(const void *const *grads, int L, int64_t M, int d, int k, int dtype,
-                   int n_blocks, const int64_t *offs, double *U, double *mu, double *eig,
-                   double *C_out)
+                   int n_blocks, const int64_t *offs, int first_slice_only, double *U, double *mu,
+                   double *eig, double *C_out)
 {
     double *C = (double *)malloc(sizeof(double) * d * d);
     int rc = 0;
     for (int b = 0; b < n_blocks; ++b) {
-        gvq_oracle_moments(grads, L, M, d, dtype, offs[b], offs[b + 1], mu + (size_t)b * d, C);
+        /* Section 3, "compressor reuse": with first_slice_only the compressor of a group of
+         * slices is computed from the group's first slice alone (its L time samples) */
+        int64_t s1 = first_slice_only ? offs[b] + 1 : offs[b + 1];
+        gvq_oracle_moments(grads, L, M, d, dtype, offs[b], s1, mu + (size_t)b * d, C);
         if (C_out) memcpy(C_out + (size_t)b * d * d, C, sizeof(double) * d * d);
         int sw = gvq_oracle_basis_from_cov(C, d, k, U + (size_t)b * d * k, eig + (size_t)b * d);
         if (sw < 0 && rc == 0) rc = -1;

@@ -385,3 +385,24 @@ def test_flatten_conv_hand_example_and_structure():
     np.testing.assert_array_equal(oracle.unflatten_conv(flat, 5, 3, 2, 4), g)
     # every run of F numbers holds one (d, h, w) position of all filters
     np.testing.assert_array_equal(flat[7 * 5:8 * 5], g[:, 7 % 3, (7 // 3) // 4, (7 // 3) % 4])
+
+
+def test_first_slice_sampling_mode():
+    """Section 3, compressor reuse: the basis of a group of slices is fitted on the L time
+    samples of the group's first slice only -- equal to a fit on those slices cut out by hand."""
+    d, k, L = 8, 3, 12
+    rng = np.random.default_rng(17)
+    offs = [0, 10, 25, 40]
+    M = 40 * d
+    grads = [g * np.float32(1 + i % 3) for i, g in enumerate(_rng_grads(rng, L, M))]
+    U, mu, eig, C = oracle.fit(grads, d, k, offsets=offs, first_slice_only=True, return_cov=True)
+    for b in range(3):
+        X = np.stack([g[offs[b] * d:(offs[b] + 1) * d] for g in grads]).astype(np.float64)   # L x d
+        np.testing.assert_allclose(mu[b], X.mean(axis=0), atol=1e-14)
+        np.testing.assert_allclose(C[b], np.cov(X.T, bias=True), atol=1e-13)
+        w_ref = np.linalg.eigvalsh(C[b])[::-1]
+        np.testing.assert_allclose(eig[b], w_ref, atol=1e-13)
+        np.testing.assert_allclose(C[b] @ U[b], U[b] * eig[b][:k], atol=1e-12)
+    # fewer samples than dimensions: the covariance is rank deficient (rank <= L - 1)
+    U, mu, eig = oracle.fit(grads[:4], d, k, offsets=offs, first_slice_only=True)
+    assert np.all(np.abs(eig[:, 3:]) < 1e-13) and np.all(eig[:, 2] > 1e-3)
