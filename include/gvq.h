@@ -91,6 +91,15 @@ int64_t gvq_num_slices(const gvq_basis_t* h);
 int gvq_fit_basis(gvq_basis_t* h, const void* const* grads, int L, void* stream);
 
 /*
+ * The paper's own sampling (Section 3, "compressor reuse"): like gvq_fit_basis, but the sample
+ * set of basis b is its FIRST slice only -- L samples, one per gradient -- and the resulting
+ * compressor is reused for the remaining slices of the range.  With L <= d the covariance is
+ * rank deficient (rank <= L - 1): the trailing eigenvalues are zero and only the first
+ * min(k, L - 1) columns of U are determined by the data.
+ */
+int gvq_fit_basis_first_slice(gvq_basis_t* h, const void* const* grads, int L, void* stream);
+
+/*
  * Waits for `stream`'s work, then reports on the last fit: *max_sweeps (may be NULL)
  * receives the largest Jacobi sweep count over the bases.  Returns GVQ_ENOCONV if a basis
  * hit the sweep limit, GVQ_ENONFINITE if an eigenvalue is not finite (e.g. NaN/Inf in a

@@ -171,19 +171,30 @@ fail:
 
 int64_t gvq_num_slices(const gvq_basis_t* h) { return h ? h->S : (int64_t)GVQ_EINVAL; }
 
-int gvq_fit_basis(gvq_basis_t* h, const void* const* grads, int L, void* stream)
+static int fit_call(gvq_basis_t* h, const void* const* grads, int L, bool first_slice_only, void* stream)
 {
     if (!h || !grads || L < 1) return GVQ_EINVAL;
     for (int l = 0; l < L; ++l) {
         if (!grads[l]) return GVQ_EINVAL;
         if (!aligned16(grads[l])) return GVQ_EALIGN;
     }
-    int rc = gvq_launch_fit(h, grads, L, (hipStream_t)stream);
+    int rc = gvq_launch_fit(h, grads, L, first_slice_only, (hipStream_t)stream);
     if (rc != GVQ_OK) return rc;
     h->fitted = true;
     h->has_cov = true;
     h->fit_L = L;
+    h->fit_first_slice = first_slice_only;
     return GVQ_OK;
+}
+
+int gvq_fit_basis(gvq_basis_t* h, const void* const* grads, int L, void* stream)
+{
+    return fit_call(h, grads, L, false, stream);
+}
+
+int gvq_fit_basis_first_slice(gvq_basis_t* h, const void* const* grads, int L, void* stream)
+{
+    return fit_call(h, grads, L, true, stream);
 }
 
 int gvq_fit_status(const gvq_basis_t* h, int* max_sweeps, void* stream)
@@ -334,7 +345,7 @@ int gvq_basis_export_cov(const gvq_basis_t* h, double* cov, int64_t* n_samples)
         for (size_t b = 0; b < B; ++b) {
             int64_t hi = h->h_offs[b + 1] < full ? h->h_offs[b + 1] : full;
             int64_t cnt = hi > h->h_offs[b] ? hi - h->h_offs[b] : 0;
-            n_samples[b] = cnt * h->fit_L;
+            n_samples[b] = (h->fit_first_slice ? (cnt > 0 ? 1 : 0) : cnt) * h->fit_L;
         }
     }
     return GVQ_OK;

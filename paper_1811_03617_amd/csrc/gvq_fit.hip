@@ -343,6 +343,7 @@ struct EigArgs {
     const int64_t* offs;
     int64_t M;
     int L, d, k;
+    int first_slice_only;  // samples of a basis: its first slice only (one per gradient)
     double* cov;           // [B][d][d]
     double* V;             // [B][n][n]
     double* eig;           // [B][d]
@@ -384,7 +385,7 @@ __global__ void eigen_kernel(EigArgs a)
     const double* mom = a.mom + (size_t)b * W;
     const int64_t full = a.M / d;
     int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
-    const double ns = hi > lo ? (double)((hi - lo) * (int64_t)a.L) : 0.0;
+    const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
     const double inv = ns > 0.0 ? 1.0 / ns : 0.0;
 
     double* V = a.V + (size_t)b * n * n;
@@ -504,6 +505,27 @@ __global__ void eigen_kernel(EigArgs a)
     if (tid == 0) a.sweeps[b] = sweeps_used;
 }
 
+// Section 3, "compressor reuse": moments of the first slice of every basis only -- L samples of d
+// numbers per basis, a few KB; one work-group per basis, one thread per matrix entry.
+__global__ void first_slice_moments_kernel(gvq_ptrs grads, int L, const int64_t* offs, int64_t M, int d, int bf16,
+                                           int accumulate, double* mom)
+{
+    const int b = blockIdx.x, W = d * d + d;
+    const int64_t j = offs[b];
+    const bool ok = (j + 1) * d <= M;     // the first slice must be a full one
+    for (int i = threadIdx.x; i < W; i += blockDim.x) {
+        const int r = i < d * d ? i / d : i - d * d, c = i < d * d ? i % d : -1;
+        double acc = 0.0;
+        if (ok)
+            for (int l = 0; l < L; ++l) {
+                const double xr = (double)load_elem(grads.p[l], bf16 != 0, j * d + r);
+                acc += c >= 0 ? xr * (double)load_elem(grads.p[l], bf16 != 0, j * d + c) : xr;
+            }
+        double* o = mom + (size_t)b * W + i;
+        *o = accumulate ? *o + acc : acc;
+    }
+}
+
 // Section 3, Eq. (5): smallest k with (eig[0] + .. + eig[k-1]) / sum(eig) >= 1 - lambda; one
 // thread per basis, partial sums from the largest eigenvalue down, in double.
 __global__ void select_k_kernel(const double* eig, int d, int B, double lambda, int* k_out)
@@ -565,10 +587,19 @@ bool gvq_moments_mfma_shape(int d) { return d == 16 || d == 32 || d == 64 || d =
 int gvq_moments_packed_width(int d) { return mom_packed_width(d); }
 int gvq_moments_streams(int d) { return d == 128 ? 2 : 4; }
 
-int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st)
+int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_slice_only, hipStream_t st)
 {
     const int d = h->d, W = d * d + d;
-    if (gvq_moments_mfma_shape(d)) {
+    if (first_slice_only) {
+        for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
+            gvq_ptrs p;
+            const int n = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
+            for (int i = 0; i < n; ++i) p.p[i] = grads[l0 + i];
+            hipLaunchKernelGGL(first_slice_moments_kernel, dim3(h->B), dim3(256), 0, st, p, n, h->d_offs, h->M, d,
+                               h->dtype == GVQ_BF16 ? 1 : 0, l0 > 0 ? 1 : 0, h->d_mom);
+            GVQ_HIP(hipGetLastError());
+        }
+    } else if (gvq_moments_mfma_shape(d)) {
         const int WP = mom_packed_width(d);
         for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
             MomMfmaArgs a;
@@ -616,6 +647,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st
 
     EigArgs e;
     e.mom = h->d_mom; e.offs = h->d_offs; e.M = h->M; e.L = L; e.d = d; e.k = h->k;
+    e.first_slice_only = first_slice_only ? 1 : 0;
     e.cov = h->d_cov; e.V = h->d_V; e.eig = h->d_eig; e.U = h->d_U; e.mu = h->d_mu;
     e.sweeps = h->d_sweeps; e.max_sweeps = 60; e.tol = 1e-15;
     const size_t lds = gvq_eigen_lds_bytes(d);

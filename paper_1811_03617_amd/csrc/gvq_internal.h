@@ -36,6 +36,7 @@ struct gvq_basis {
     int loss_groups = 1;
     int P = 0;                  // moment partials per basis
     int fit_L = 0;              // gradients of the last fit
+    bool fit_first_slice = false;  // the last fit sampled only the first slice of every basis
     bool fitted = false;        // basis usable (fit or import)
     bool has_cov = false;       // d_cov / d_eig hold a fit's results
 };
@@ -65,7 +66,7 @@ int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, f
                          hipStream_t st);
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                           void* out, gvq_dtype_t odt, hipStream_t st);
-int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
+int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_slice_only, hipStream_t st);
 int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
                           hipStream_t st);
 int gvq_launch_layout(const void* src, void* dst, int F, int D, int HW, gvq_dtype_t dtype, bool flatten,

@@ -42,6 +42,7 @@ def lib():
         L.gvq_num_slices.argtypes = [vp]
         L.gvq_num_slices.restype = i64
         L.gvq_fit_basis.argtypes = [vp, C.POINTER(vp), i32, vp]
+        L.gvq_fit_basis_first_slice.argtypes = [vp, C.POINTER(vp), i32, vp]
         L.gvq_fit_status.argtypes = [vp, C.POINTER(i32), vp]
         L.gvq_compress.argtypes = [vp, vp, i32, vp, vp]
         L.gvq_aggregate.argtypes = [vp, C.POINTER(vp), i32, vp, vp]
@@ -62,7 +63,7 @@ def lib():
                      "gvq_compress", "gvq_aggregate", "gvq_decompress", "gvq_basis_export",
                      "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option", "gvq_local_loss",
                      "gvq_select_k", "gvq_compress_segment", "gvq_decompress_segment", "gvq_flatten_conv",
-                     "gvq_unflatten_conv"):
+                     "gvq_unflatten_conv", "gvq_fit_basis_first_slice"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -121,6 +122,11 @@ def gvq_num_slices(h):
 def gvq_fit_basis(h, grads, stream=None):
     arr = (C.c_void_p * len(grads))(*[_ptr(g) for g in grads])
     _check(lib().gvq_fit_basis(h, arr, len(grads), _stream(stream)), "gvq_fit_basis")
+
+
+def gvq_fit_basis_first_slice(h, grads, stream=None):
+    arr = (C.c_void_p * len(grads))(*[_ptr(g) for g in grads])
+    _check(lib().gvq_fit_basis_first_slice(h, arr, len(grads), _stream(stream)), "gvq_fit_basis_first_slice")
 
 
 def gvq_fit_status(h, stream=None):
@@ -202,8 +208,11 @@ class Basis:
     def handle(self):
         return self._h
 
-    def fit(self, grads, stream=None):
-        gvq_fit_basis(self._h, grads, stream)
+    def fit(self, grads, stream=None, first_slice_only=False):
+        if first_slice_only:
+            gvq_fit_basis_first_slice(self._h, grads, stream)
+        else:
+            gvq_fit_basis(self._h, grads, stream)
 
     def fit_status(self, stream=None):
         return gvq_fit_status(self._h, stream)

@@ -144,3 +144,37 @@ def test_fit_then_codec_end_to_end_loss_matches_discarded_eigenvalues():
     b.close()
     lost = eig[0][w.k:].sum()
     assert abs(err / (len(fit) * w.S) - lost) < 1e-4 * eig[0].sum()
+
+
+@pytest.mark.parametrize("M,d,k,L,block_elems,dtype", [
+    (64 * 400, 64, 8, 100, 64 * 50, "f32"),      # the paper's L_t = 100 time samples, 8 bases
+    (128 * 300 + 40, 128, 16, 40, 128 * 64, "bf16"),   # fewer samples than dimensions
+    (16 * 900 + 3, 16, 4, 37, 0, "f32"),
+    (24 * 100, 24, 5, 9, 24 * 30, "f32"),
+])
+def test_fit_first_slice_sampling_mode(M, d, k, L, block_elems, dtype):
+    """Section 3 'compressor reuse': L time samples of the first slice of every basis."""
+    w = _wl(M, d, k, 2, L, dtype=dtype, block_elems=block_elems, rank=min(6, d // 2), sigma=0.3)
+    fit = synth.fit_gradients(w, "cpu")
+    offs = w.block_offsets()
+    Uo, muo, eigo, Co = oracle.fit([synth.to_numpy(g) for g in fit], d, k, dtype=dtype, offsets=offs,
+                                   first_slice_only=True, return_cov=True)
+    b = gvq.Basis(M, d, k, offs, dtype)
+    b.fit([g.to(DEV) for g in fit], first_slice_only=True)
+    assert 0 <= b.fit_status() < 40
+    U, mu, eig = b.export()
+    C, n = b.export_cov()
+    b.close()
+    for bb in range(w.n_blocks):
+        assert n[bb] == L
+        lam1 = eigo[bb][0]
+        np.testing.assert_allclose(mu[bb], muo[bb], rtol=2e-7, atol=1e-7 * np.sqrt(lam1))
+        assert np.max(np.abs(C[bb] - Co[bb])) <= 1e-12 * lam1
+        np.testing.assert_allclose(eig[bb], eigo[bb], rtol=0, atol=1e-11 * lam1)
+        kk = min(k, L - 1)                      # what the data determines
+        # leave out columns whose eigenvalue is not separated from its neighbours
+        while kk > 1 and eigo[bb][kk - 1] - eigo[bb][kk] < 1e-6 * lam1:
+            kk -= 1
+        assert max_angle(U[bb][:, :kk].astype(np.float64), Uo[bb][:, :kk]) < ANGLE_TOL
+        Ub = U[bb].astype(np.float64)
+        assert np.max(np.abs(Ub.T @ Ub - np.eye(k))) < 1e-5
