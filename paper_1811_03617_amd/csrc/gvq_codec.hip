@@ -795,15 +795,20 @@ static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_
     return a;
 }
 
-template <typename K>
-static int streaming_grid(const gvq_basis* h, K kernel, int64_t tiles)
+template <auto KERN>
+static int streaming_grid(const gvq_basis* h, int64_t tiles)
 {
     int per_cu = gvq_opt_wg_per_cu();
     if (per_cu <= 0) {
-        int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, WG_THREADS, 0) != hipSuccess || occ < 1)
-            occ = 2;
-        per_cu = occ;
+        // one instance of this function per kernel: ask the runtime once, then remember
+        static int cached = 0;
+        if (cached == 0) {
+            int occ = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, KERN, WG_THREADS, 0) != hipSuccess || occ < 1)
+                occ = 2;
+            cached = occ;
+        }
+        per_cu = cached;
     }
     int64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;  // at least one tile per wave
     int64_t cap = (int64_t)h->num_cu * per_cu;
@@ -826,9 +831,9 @@ static int run_length(const gvq_basis* h, int64_t tiles, int grid)
 template <int D, int NT, bool BF16, int VAR>
 static int launch_compress_v(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false>;
+    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false>;
     int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid(h, kern, tiles);
+    int grid = streaming_grid<kern>(h, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
@@ -856,9 +861,9 @@ static int launch_compress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t
 template <int D, int NT, bool ACC>
 static int launch_compress_bf16_a(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = compress_bf16_kernel<D, NT, ACC>;
+    constexpr auto kern = compress_bf16_kernel<D, NT, ACC>;
     int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid(h, kern, tiles);
+    int grid = streaming_grid<kern>(h, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
@@ -917,9 +922,9 @@ int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int
 template <int D, int NQ, bool OBF>
 static int launch_decompress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = decompress_mfma_kernel<D, NQ, OBF>;
+    constexpr auto kern = decompress_mfma_kernel<D, NQ, OBF>;
     int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid(h, kern, tiles);
+    int grid = streaming_grid<kern>(h, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
@@ -1072,9 +1077,9 @@ __global__ __launch_bounds__(256) void loss_reduce2_kernel(const double* part, i
 template <int D, int NT, bool BF16>
 static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    auto kern = compress_mfma_kernel<D, NT, BF16, 0, true>;
+    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, 0, true>;
     int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid(h, kern, tiles);
+    int grid = streaming_grid<kern>(h, tiles);
     CodecArgs b = a;
     b.run_tiles = run_length(h, tiles, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
