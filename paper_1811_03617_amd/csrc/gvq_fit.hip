@@ -386,7 +386,6 @@ __global__ void eigen_kernel(EigArgs a)
     const int64_t full = a.M / d;
     int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
     const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
-    const double inv = ns > 0.0 ? 1.0 / ns : 0.0;
 
     double* V = a.V + (size_t)b * n * n;
     double* cov = a.cov + (size_t)b * d * d;
@@ -396,14 +395,15 @@ __global__ void eigen_kernel(EigArgs a)
         double v = 0.0;
         if (r < d && c < d) {
             // upper and lower halves of the Gram sum are bit-identical (same products, same order)
-            v = mom[r * d + c] * inv - (mom[d * d + r] * inv) * (mom[d * d + c] * inv);
+            // true divisions: a constant gradient then gives exactly C = 0
+            v = ns > 0.0 ? mom[r * d + c] / ns - (mom[d * d + r] / ns) * (mom[d * d + c] / ns) : 0.0;
             cov[r * d + c] = v;
         }
         A[i] = v;
         V[i] = r == c ? 1.0 : 0.0;
         fro2 += v * v;
     }
-    for (int i = tid; i < d; i += nth) a.mu[(size_t)b * d + i] = (float)(mom[d * d + i] * inv);
+    for (int i = tid; i < d; i += nth) a.mu[(size_t)b * d + i] = ns > 0.0 ? (float)(mom[d * d + i] / ns) : 0.0f;
     fro2 = block_sum(fro2, red);
 
     int sweeps_used = -1;

@@ -209,3 +209,14 @@ def test_error_paths_on_the_device():
     assert L.gvq_compress(b.handle, x.data_ptr(), 1, y.data_ptr(), st) == gvq.OK
     torch.cuda.synchronize()
     b.close()
+
+
+def test_codec_is_bitwise_reproducible():
+    w = _wl(128 * 2000 + 40, 128, 32, 3)
+    U32, mu32 = _oracle_basis(w)
+    dev = [g.to(DEV) for g in synth.worker_gradients(w, "cpu")]
+    a = _run_codec(w, U32, mu32, dev)
+    b = _run_codec(w, U32, mu32, dev)
+    for x, y in zip(a[0], b[0]):
+        assert np.array_equal(x, y)
+    assert np.array_equal(a[1], b[1]) and torch.equal(a[2], b[2])

@@ -178,3 +178,33 @@ def test_fit_first_slice_sampling_mode(M, d, k, L, block_elems, dtype):
         assert max_angle(U[bb][:, :kk].astype(np.float64), Uo[bb][:, :kk]) < ANGLE_TOL
         Ub = U[bb].astype(np.float64)
         assert np.max(np.abs(Ub.T @ Ub - np.eye(k))) < 1e-5
+
+
+def test_fit_degenerate_inputs():
+    """Constant gradients (zero covariance) and rank-one data (all but one eigenvalue zero)."""
+    M, d, k = 32 * 500, 32, 4
+    const = [torch.full((M,), 0.75), torch.full((M,), 0.75)]
+    Uo, muo, eigo = oracle.fit([synth.to_numpy(g) for g in const], d, k)
+    b = gvq.Basis(M, d, k)
+    b.fit([g.to(DEV) for g in const])
+    assert b.fit_status() == 0
+    U, mu, eig = b.export()
+    assert np.all(eig == 0) and np.all(eigo == 0)
+    np.testing.assert_array_equal(mu[0], np.full(d, 0.75, np.float32))
+    np.testing.assert_array_equal(U[0], np.eye(d, k, dtype=np.float32))
+    np.testing.assert_array_equal(Uo[0], np.eye(d, k))
+    # rank one: every slice is a multiple of one direction v, with zero mean overall
+    gen = torch.Generator().manual_seed(8)
+    v = torch.randn(d, generator=gen)
+    coef = torch.randn(M // d, generator=gen)
+    g1 = (coef[:, None] * v[None, :]).reshape(-1).contiguous()
+    Uo, muo, eigo = oracle.fit([synth.to_numpy(g1)], d, k)
+    b.fit([g1.to(DEV)])
+    b.fit_status()
+    U, mu, eig = b.export()
+    b.close()
+    assert abs(eig[0][0] - eigo[0][0]) < 1e-10 * eigo[0][0]
+    assert np.all(np.abs(eig[0][1:]) < 1e-9 * eigo[0][0])
+    assert max_angle(U[0][:, :1].astype(np.float64), Uo[0][:, :1]) < ANGLE_TOL
+    vn = (v / v.norm()).numpy().astype(np.float64)
+    assert abs(abs(np.dot(U[0][:, 0], vn)) - 1) < 1e-6
