@@ -510,16 +510,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
     int cur_b = block_of_tile(a, it.t);
     int64_t blk_begin = a.offs[cur_b], blk_end = a.offs[cur_b + 1];
     f4 uf[ET][NQ];   // uf[et][q][j] = U[16et + n_][16q + 4kk + j], zero past column k
-    f4 mu4[ET];
+    float mul[EPS];  // mu of the elements this lane writes out (the same chunk of every slice)
     auto load_basis = [&](int b) {
         const f4* Up = a.Upack + (size_t)b * (ET * NQ * 64) + lane;
-        const f4* mub = (const f4*)(a.mu + (size_t)b * D) + kk;
+        const float* mub = a.mu + (size_t)b * D + (lane % SCPS) * EPS;
 #pragma unroll
-        for (int et = 0; et < ET; ++et) {
+        for (int et = 0; et < ET; ++et)
 #pragma unroll
             for (int q = 0; q < NQ; ++q) uf[et][q] = Up[(et * NQ + q) * 64];
-            mu4[et] = mub[4 * et];
-        }
+#pragma unroll
+        for (int i = 0; i < EPS; ++i) mul[i] = mub[i];
     };
     load_basis(cur_b);
 
@@ -581,7 +581,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
             wave_lds_sync();
 #pragma unroll
             for (int et = 0; et < ET; ++et) {
-                f4 acc = mu4[et];
+                f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
@@ -601,8 +601,13 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
                 const int s = g / SCPS, c = g % SCPS;
                 const int64_t e0 = s0 * D + (int64_t)g * EPS;
                 if (OUT_BF16) {
-                    const f4 v0 = lds[s * CPS + ((2 * c) ^ swz<D>(s))];
-                    const f4 v1 = lds[s * CPS + ((2 * c + 1) ^ swz<D>(s))];
+                    f4 v0 = lds[s * CPS + ((2 * c) ^ swz<D>(s))];
+                    f4 v1 = lds[s * CPS + ((2 * c + 1) ^ swz<D>(s))];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v0[i] += mul[i];
+                        v1[i] += mul[(4 + i) % EPS];
+                    }
                     unsigned short* o = (unsigned short*)a.out;
                     if (whole || (s0 + s >= lo && s0 + s < hi && e0 + 8 <= a.M)) {
                         u4 pk = {pack_bf16x2(v0[0], v0[1]), pack_bf16x2(v0[2], v0[3]),
@@ -616,7 +621,9 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
                         }
                     }
                 } else {
-                    const f4 v = lds[s * CPS + (c ^ swz<D>(s))];
+                    f4 v = lds[s * CPS + (c ^ swz<D>(s))];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] += mul[i];
                     float* o = (float*)a.out;
                     if (whole || (s0 + s >= lo && s0 + s < hi && e0 + 4 <= a.M)) {
                         stream_store((f4*)(o + e0), v);
