@@ -55,7 +55,7 @@ typedef enum {
     GVQ_ENOCONV = -7     /* gvq_fit_status: the eigensolver hit its sweep limit */
 } gvq_status_t;
 
-#define GVQ_MAX_D 128 /* largest supported slice length */
+#define GVQ_MAX_D 1024 /* largest supported slice length */
 
 /*
  * Create the codec state for gradients of n_elems (M >= 1) elements of grad_dtype, slice

@@ -22,7 +22,7 @@ from . import build as _build
 
 _lib = None
 _DT = {"f32": 0, "bf16": 1}
-MAX_D = 512
+MAX_D = 1024
 
 
 def lib():

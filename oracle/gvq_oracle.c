@@ -46,6 +46,7 @@
 #endif
 
 enum { GO_F32 = 0, GO_BF16 = 1 };
+#define ORACLE_MAX_D 1024 /* largest slice length (size of the per-slice stack buffers) */
 
 /* Widen element idx of a stored gradient to double. bf16 is the upper half of an fp32. */
 static double load_elem(const void *g, int dtype, int64_t idx)
@@ -179,7 +180,7 @@ int64_t gvq_oracle_moments(const void *const *grads, int L, int64_t M, int d, in
         int t = 0;
 #endif
         double *acc = part + (size_t)t * (size_t)(d * d);
-        double x[512];
+        double x[ORACLE_MAX_D];
         for (int l = 0; l < L; ++l) {
 #pragma omp for schedule(static)
             for (int64_t j = s0; j < s1; ++j) {
@@ -202,7 +203,7 @@ int64_t gvq_oracle_moments(const void *const *grads, int L, int64_t M, int d, in
         int t = 0;
 #endif
         double *acc = part + (size_t)t * (size_t)(d * d);
-        double x[512];
+        double x[ORACLE_MAX_D];
         for (int l = 0; l < L; ++l) {
 #pragma omp for schedule(static)
             for (int64_t j = s0; j < s1; ++j) {
@@ -340,7 +341,7 @@ void gvq_oracle_compress(const void *grad, int64_t M, int d, int k, int dtype, i
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = j0; j < j1; ++j) {
-        double x[512];
+        double x[ORACLE_MAX_D];
         int b = block_of(j, n_blocks, offs);
         const double *Ub = U + (size_t)b * d * k, *mub = mu + (size_t)b * d;
         load_slice(grad, dtype, M, d, j, x);
@@ -424,7 +425,7 @@ void gvq_oracle_local_loss(const void *grad, int64_t M, int d, int k, int dtype,
         int64_t j0 = offs[b], j1 = offs[b + 1] < S ? offs[b + 1] : S;
 #pragma omp parallel for schedule(static) reduction(+ : acc)
         for (int64_t j = j0; j < j1; ++j) {
-            double x[512], y[512];
+            double x[ORACLE_MAX_D], y[ORACLE_MAX_D];
             load_slice(grad, dtype, M, d, j, x);
             for (int e = 0; e < d; ++e) x[e] -= mub[e] / (double)n_workers;
             for (int i = 0; i < k; ++i) {

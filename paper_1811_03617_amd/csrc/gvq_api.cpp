@@ -56,7 +56,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_jac, h->d_jstate, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
@@ -102,7 +102,17 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipGetDeviceProperties(&prop, h->device));
         h->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
         size_t width = (size_t)d * d + d;
-        if (gvq_moments_mfma_shape(d)) {
+        size_t part_doubles = 0;   // per basis, when not P * width
+        if (d > GVQ_LDS_EIGEN_MAX_D) {
+            // one wave per (64 x 64 block, sample chunk): enough chunks for about two waves per
+            // SIMD over all bases, never less than 64 sample slices per chunk
+            const int64_t ng = gvq_large_groups(d), npairs = ng * (ng + 1) / 2;
+            int64_t chunks = (8LL * h->num_cu + npairs * n_blocks - 1) / (npairs * n_blocks);
+            if (chunks > (longest + 63) / 64) chunks = (longest + 63) / 64;
+            if (chunks < 1) chunks = 1;
+            h->P = (int)chunks;
+            part_doubles = gvq_large_partial_doubles(d, h->P);
+        } else if (gvq_moments_mfma_shape(d)) {
             // two work-groups of 4 waves per compute unit, spread over the bases; never less
             // than 64 sample slices per stream
             const int streams = gvq_moments_streams(d);
@@ -134,8 +144,14 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
         TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
-        TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * width));
-        TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));
+        if (part_doubles) {
+            TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * part_doubles));
+            TRY(hipMalloc((void**)&h->d_jac, sizeof(double) * B * 2 * n * n));
+            TRY(hipMalloc((void**)&h->d_jstate, sizeof(int) * B * 4));
+        } else {
+            TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * width));
+            TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));
+        }
         TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
         TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
         TRY(hipMalloc((void**)&h->d_ksel, sizeof(int) * B));

@@ -513,7 +513,7 @@ __global__ void first_slice_moments_kernel(gvq_ptrs grads, int L, const int64_t*
     const int b = blockIdx.x, W = d * d + d;
     const int64_t j = offs[b];
     const bool ok = (j + 1) * d <= M;     // the first slice must be a full one
-    for (int i = threadIdx.x; i < W; i += blockDim.x) {
+    for (int i = blockIdx.y * blockDim.x + threadIdx.x; i < W; i += gridDim.y * blockDim.x) {
         const int r = i < d * d ? i / d : i - d * d, c = i < d * d ? i % d : -1;
         double acc = 0.0;
         if (ok)
@@ -595,10 +595,14 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
             gvq_ptrs p;
             const int n = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
             for (int i = 0; i < n; ++i) p.p[i] = grads[l0 + i];
-            hipLaunchKernelGGL(first_slice_moments_kernel, dim3(h->B), dim3(256), 0, st, p, n, h->d_offs, h->M, d,
+            hipLaunchKernelGGL(first_slice_moments_kernel, dim3(h->B, (W + 4095) / 4096), dim3(256), 0, st, p, n,
+                               h->d_offs, h->M, d,
                                h->dtype == GVQ_BF16 ? 1 : 0, l0 > 0 ? 1 : 0, h->d_mom);
             GVQ_HIP(hipGetLastError());
         }
+    } else if (d > GVQ_LDS_EIGEN_MAX_D) {
+        const int rc = gvq_launch_moments_large(h, grads, L, st);
+        if (rc != GVQ_OK) return rc;
     } else if (gvq_moments_mfma_shape(d)) {
         const int WP = mom_packed_width(d);
         for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
@@ -645,6 +649,10 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         GVQ_HIP(hipGetLastError());
     }
 
+    if (d > GVQ_LDS_EIGEN_MAX_D) {
+        const int rc = gvq_launch_eigen_large(h, L, first_slice_only, st);
+        return rc != GVQ_OK ? rc : gvq_launch_pack(h, st);
+    }
     EigArgs e;
     e.mom = h->d_mom; e.offs = h->d_offs; e.M = h->M; e.L = L; e.d = d; e.k = h->k;
     e.first_slice_only = first_slice_only ? 1 : 0;
@@ -654,7 +662,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
     static bool attr_set = false;
     if (!attr_set) {
         GVQ_HIP(hipFuncSetAttribute((const void*)eigen_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)gvq_eigen_lds_bytes(GVQ_MAX_D)));
+                                    (int)gvq_eigen_lds_bytes(GVQ_LDS_EIGEN_MAX_D)));
         attr_set = true;
     }
     const int threads = d > 64 ? 1024 : (d > 16 ? 256 : 64);

@@ -6,6 +6,7 @@
 #include "gvq.h"
 
 #define GVQ_MAX_PTRS 32  // device pointers passed by value in one kernel launch
+#define GVQ_LDS_EIGEN_MAX_D 128  // longest slice whose d x d matrix the one-work-group eigensolver holds in LDS
 
 struct gvq_basis {
     int64_t M = 0, S = 0;       // elements, slices
@@ -29,6 +30,8 @@ struct gvq_basis {
     double* d_part2 = nullptr;  // [B][ceil(P/32)][width] second level of the partial sum (MFMA path)
     int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
+    double* d_jac = nullptr;    // [B][2][dp][dp] matrix buffers of the global-memory Jacobi (d > 128 only)
+    int* d_jstate = nullptr;    // [B][4] its per-basis state (d > 128 only)
     int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
     int* d_ksel = nullptr;      // [B] result of the last gvq_select_k
     float* d_loss_slice = nullptr;  // [S] per-slice squared residual of the last gvq_local_loss
@@ -79,3 +82,8 @@ bool gvq_bf16_pipe_shape(const gvq_basis* h);
 bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
+// Long slices (d > GVQ_LDS_EIGEN_MAX_D): moments in 64 x 64 blocks, Jacobi out of global memory.
+int gvq_large_groups(int d);
+size_t gvq_large_partial_doubles(int d, int chunks);   // per basis
+int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
+int gvq_launch_eigen_large(gvq_basis* h, int L, bool first_slice_only, hipStream_t st);

@@ -14,7 +14,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 OK, EINVAL, EALIGN, ENOTFIT, EHIP, ENOMEM, ENONFINITE, ENOCONV = 0, -1, -2, -3, -4, -5, -6, -7
-MAX_D = 128
+MAX_D = 1024
 
 _lib = None
 
