@@ -41,7 +41,7 @@ def test_strerror_and_option_checks():
 @pytest.mark.parametrize("M,d,k,nb,offs", [
     (0, 16, 4, 1, None),        # no elements
     (100, 1, 1, 1, None),       # d too small
-    (100, 129, 4, 1, None),     # d too large
+    (100, 1025, 4, 1, None),    # d too large
     (100, 16, 0, 1, None),      # k too small
     (100, 16, 17, 1, None),     # k > d
     (100, 16, 4, 2, None),      # several bases need offsets
