@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgvq.so")
-SOURCES = ["gvq_api.cpp", "gvq_codec.hip", "gvq_fit.hip", "gvq_fit_large.hip", "gvq_layout.hip"]
+SOURCES = ["gvq_api.cpp", "gvq_codec.hip", "gvq_codec_long.hip", "gvq_fit.hip", "gvq_fit_large.hip", "gvq_layout.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -56,10 +56,11 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_jac, h->d_jstate, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_jac, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     free(h->h_offs);
+    free(h->h_ltile);
     delete h;
     (void)hipGetLastError();
     return GVQ_OK;
@@ -132,7 +133,20 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_offs, sizeof(int64_t) * (B + 1)));
         TRY(hipMalloc((void**)&h->d_U, sizeof(float) * B * d * k));
         TRY(hipMalloc((void**)&h->d_mu, sizeof(float) * B * d));
-        if (gvq_mfma_shape(d, k)) {
+        if (gvq_long_shape(d, k)) {
+            const size_t pf = gvq_long_pack_floats(d, k);
+            TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * pf));
+            TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * pf));
+            if (n_blocks > 1) {
+                h->h_ltile = (int64_t*)malloc(sizeof(int64_t) * (B + 1));
+                if (!h->h_ltile) { rc = GVQ_ENOMEM; goto fail; }
+                h->h_ltile[0] = 0;
+                for (int b = 0; b < n_blocks; ++b)
+                    h->h_ltile[b + 1] = h->h_ltile[b] + gvq_long_tiles(h->h_offs[b + 1] - h->h_offs[b]);
+                TRY(hipMalloc((void**)&h->d_ltile, sizeof(int64_t) * (B + 1)));
+                TRY(hipMemcpy(h->d_ltile, h->h_ltile, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice));
+            }
+        } else if (gvq_mfma_shape(d, k)) {
             const size_t kp = k <= 16 ? 16 : 32;
             TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * d * kp));
             TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * d * kp));

@@ -789,6 +789,7 @@ bool gvq_bf16_pipe_shape(const gvq_basis* h)
 
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st)
 {
+    if (gvq_long_shape(h->d, h->k)) return gvq_launch_pack_long(h, st);
     if (!gvq_mfma_shape(h->d, h->k)) return GVQ_OK;
     hipLaunchKernelGGL(pack_basis_kernel, dim3(h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd,
                        h->d, h->k, h->k <= 16 ? 1 : 2);
@@ -908,6 +909,8 @@ static int launch_compress_bf16_d(const gvq_basis* h, const CodecArgs& a, hipStr
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
                         int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
+    if (gvq_long_shape(h->d, h->k))
+        return gvq_launch_compress_long(h, grad, n_workers, first_slice, n_slices, comp_in, out, st);
     if (gvq_bf16_pipe_shape(h)) {
         CodecArgs a = make_args(h, grad, out, n_workers, (const float*)h->d_Upb);
         a.Umu = h->d_Umu;
@@ -963,6 +966,7 @@ static int launch_decompress_d(const gvq_basis* h, const CodecArgs& a, hipStream
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                           void* out, gvq_dtype_t odt, hipStream_t st)
 {
+    if (gvq_long_shape(h->d, h->k)) return gvq_launch_decompress_long(h, comp, first_slice, n_slices, out, odt, st);
     CodecArgs a = make_args(h, comp, out, 1, h->d_Upd);
     a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
     const bool bf = odt == GVQ_BF16;

@@ -1,0 +1,422 @@
+// Codec kernels for long slices, 128 < d <= GVQ_MAX_D and k <= 128 (GradiVeQ Eqs. 2 and 4 with
+// the slice sizes of Section 3, e.g. d = 768).  U (d x k floats, up to 512 KB) no longer fits a
+// wave's registers, so these are LDS-tiled contractions on v_mfma_f32_16x16x4_f32:
+//   a work-group of 4 waves owns LW_SLICES = 128 consecutive slices of one basis, 32 per wave
+//   (two 16-slice MFMA column tiles);  U is streamed through LDS in chunks of LC = 64 elements,
+//   double-buffered, one s_barrier per chunk, shared by the 4 waves;  the gradient side goes
+//   straight between global memory and registers in MFMA operand order (lane (n, kk) moves 4
+//   consecutive elements of slice n with one 128-bit access).
+// Tiles never straddle two bases: the tiles of basis b are tstart[b] .. tstart[b+1]-1.
+#include "gvq_device.h"
+
+#define LW_SLICES 128
+#define LC 64
+
+struct LongArgs {
+    const void* in;
+    void* out;
+    const float* acc_in;     // compress only, may be null
+    const f4* Upack;         // [B][nchunk][4][NT][64] f4 in the kernel's operand order
+    const float* mu;         // [B][d]
+    const int64_t* offs;     // [B+1]
+    const int64_t* tstart;   // [B+1] first tile of each basis (B > 1 only)
+    int64_t M, S, seg_begin, seg_end, t0, t1;
+    int B, d, k, nchunk;
+    float n_workers;
+};
+
+__device__ __forceinline__ void long_tile(const LongArgs& a, int64_t tile, int& b, int64_t& first, int64_t& end)
+{
+    if (a.B == 1) {
+        b = 0;
+        first = tile * LW_SLICES;
+        end = first + LW_SLICES < a.S ? first + LW_SLICES : a.S;
+        return;
+    }
+    int lo = 0, hi = a.B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.tstart[mid] <= tile) lo = mid; else hi = mid;
+    }
+    b = lo;
+    first = a.offs[b] + (tile - a.tstart[b]) * LW_SLICES;
+    end = first + LW_SLICES < a.offs[b + 1] ? first + LW_SLICES : a.offs[b + 1];
+}
+
+// 4 consecutive gradient elements starting at element e of slice s, zero where the slice or the
+// gradient ends (the zero padding of the last slice).
+template <bool BF16>
+__device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s, int e)
+{
+    f4 v = {0.f, 0.f, 0.f, 0.f};
+    if (!row_ok || e >= a.d) return v;
+    const int64_t idx = s * a.d + e;
+    if ((a.d & 3) == 0 && idx + 3 < a.M) {
+        if (BF16) {
+            const u2 w = *(const u2*)((const unsigned short*)a.in + idx);
+            v[0] = __uint_as_float(w.x << 16);
+            v[1] = __uint_as_float(w.x & 0xffff0000u);
+            v[2] = __uint_as_float(w.y << 16);
+            v[3] = __uint_as_float(w.y & 0xffff0000u);
+        } else {
+            v = *(const f4*)((const float*)a.in + idx);
+        }
+        return v;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (e + r < a.d && idx + r < a.M)
+            v[r] = BF16 ? bf16_to_f32(((const unsigned short*)a.in)[idx + r]) : ((const float*)a.in)[idx + r];
+    return v;
+}
+
+// --------------------------------------------------------------------------------------
+// compress: D[comp][slice] += U[elem][comp] x[slice][elem].  For chunk c, load i (0..3) and
+// step j (0..3), lane (m, kk) of the A operand holds U[64c + 16i + 4kk + j][16nt + m] and lane
+// (n, kk) of the B operand x[slice n][64c + 16i + 4kk + j] - mu/N: one 128-bit word of x feeds
+// four steps.  Result register r of lane (n, kk) is comp 16nt + 4kk + r of slice n.
+// Upack[b][c][i][nt][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
+// --------------------------------------------------------------------------------------
+template <int NT, bool BF16>
+__global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
+{
+    extern __shared__ f4 smem[];
+    constexpr int CH4 = 4 * NT * 64;              // 128-bit words of one U chunk
+    f4* Us = smem;                                // [2][CH4]
+    float* mus = (float*)(smem + 2 * CH4);        // [nchunk * LC]  mu / N, zero past d
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_ = lane & 15, kk = lane >> 4;
+
+    for (int64_t tile = a.t0 + blockIdx.x; tile < a.t1; tile += gridDim.x) {
+        int b;
+        int64_t first, end;
+        long_tile(a, tile, b, first, end);
+        const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
+        const f4* Ub = a.Upack + (size_t)b * a.nchunk * CH4;
+        __syncthreads();   // the previous tile's readers are done with mus and Us
+        for (int e = tid; e < a.nchunk * LC; e += 256)
+            mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] / a.n_workers : 0.f;
+        f4 ur[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
+        __syncthreads();
+
+        int64_t s[2];
+        bool ok[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            s[t] = first + wave * 32 + 16 * t + n_;
+            ok[t] = s[t] >= lo && s[t] < hi;
+        }
+        f4 acc[2][NT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[t][nt] = f4{0.f, 0.f, 0.f, 0.f};
+        f4 xr[2][4], xn[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16>(a, ok[t], s[t], 16 * i + 4 * kk);
+
+        for (int c = 0; c < a.nchunk; ++c) {
+            const bool more = c + 1 < a.nchunk;
+            if (more) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)(c + 1) * CH4 + tid + 256 * q];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        xn[t][i] = load_x4<BF16>(a, ok[t], s[t], (c + 1) * LC + 16 * i + 4 * kk);
+            }
+            const f4* Uc = Us + (c & 1) * CH4;
+            __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const f4 mw = *(const f4*)(mus + c * LC + 16 * i + 4 * kk);
+                const f4 x0 = xr[0][i] - mw, x1 = xr[1][i] - mw;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const f4 uw = Uc[(i * NT + nt) * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], x0[j], acc[0][nt], 0, 0, 0);
+                        acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], x1[j], acc[1][nt], 0, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_s_setprio(0);
+            if (more) {
+                f4* Un = Us + ((c + 1) & 1) * CH4;   // last read one chunk ago, before the previous barrier
+#pragma unroll
+                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xr[t][i] = xn[t][i];
+                __syncthreads();
+            }
+        }
+
+        float* Y = (float*)a.out;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (!ok[t]) continue;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int c0 = 16 * nt + 4 * kk;
+                if (c0 >= a.k) continue;
+                const int64_t o = s[t] * a.k + c0;
+                f4 v = acc[t][nt];
+                if ((a.k & 3) == 0) {
+                    if (a.acc_in) v += *(const f4*)(a.acc_in + o);
+                    *(f4*)(Y + o) = v;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
+                }
+            }
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------
+// decompress: D[elem][slice] = sum_comp U[elem][comp] Y[slice][comp], then + mu.  The wave keeps
+// its 32 slices of Y in registers (lane (n, kk) holds comps 16w + 4kk + j, w < NT) and walks
+// over the element chunks; for element tile et (0..3) of chunk c and comp group w, lane (m, kk)
+// of the A operand holds U[64c + 16et + m][16w + 4kk + j].  Result register r of lane (n, kk) is
+// element 64c + 16et + 4kk + r of slice n: one 128-bit store.
+// Upack[b][c][et][w][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
+// --------------------------------------------------------------------------------------
+template <int NT, bool OUT_BF16>
+__global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
+{
+    extern __shared__ f4 smem[];
+    constexpr int CH4 = 4 * NT * 64;
+    f4* Us = smem;
+    float* mus = (float*)(smem + 2 * CH4);        // [nchunk * LC]  mu, zero past d
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_ = lane & 15, kk = lane >> 4;
+    const float* Y = (const float*)a.in;
+
+    for (int64_t tile = a.t0 + blockIdx.x; tile < a.t1; tile += gridDim.x) {
+        int b;
+        int64_t first, end;
+        long_tile(a, tile, b, first, end);
+        const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
+        const f4* Ub = a.Upack + (size_t)b * a.nchunk * CH4;
+        __syncthreads();
+        for (int e = tid; e < a.nchunk * LC; e += 256) mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] : 0.f;
+        f4 ur[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
+        __syncthreads();
+
+        int64_t s[2];
+        bool ok[2];
+        f4 yr[2][NT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            s[t] = first + wave * 32 + 16 * t + n_;
+            ok[t] = s[t] >= lo && s[t] < hi;
+#pragma unroll
+            for (int w = 0; w < NT; ++w) {
+                yr[t][w] = f4{0.f, 0.f, 0.f, 0.f};
+                const int c0 = 16 * w + 4 * kk;
+                if (!ok[t] || c0 >= a.k) continue;
+                const float* p = Y + s[t] * a.k + c0;
+                if ((a.k & 3) == 0) {
+                    yr[t][w] = *(const f4*)p;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (c0 + r < a.k) yr[t][w][r] = p[r];
+                }
+            }
+        }
+
+        for (int c = 0; c < a.nchunk; ++c) {
+            const bool more = c + 1 < a.nchunk;
+            if (more) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)(c + 1) * CH4 + tid + 256 * q];
+            }
+            const f4* Uc = Us + (c & 1) * CH4;
+            f4 acc[2][4];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int et = 0; et < 4; ++et) acc[t][et] = f4{0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+            for (int et = 0; et < 4; ++et)
+#pragma unroll
+                for (int w = 0; w < NT; ++w) {
+                    const f4 uw = Uc[(et * NT + w) * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acc[0][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], yr[0][w][j], acc[0][et], 0, 0, 0);
+                        acc[1][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], yr[1][w][j], acc[1][et], 0, 0, 0);
+                    }
+                }
+            __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (!ok[t]) continue;
+#pragma unroll
+                for (int et = 0; et < 4; ++et) {
+                    const int e0 = c * LC + 16 * et + 4 * kk;
+                    if (e0 >= a.d) continue;
+                    const f4 v = acc[t][et] + *(const f4*)(mus + e0);
+                    const int64_t idx = s[t] * a.d + e0;
+                    if ((a.d & 3) == 0 && idx + 3 < a.M) {
+                        if (OUT_BF16) {
+                            u2 w2;
+                            w2.x = pack_bf16x2(v[0], v[1]);
+                            w2.y = pack_bf16x2(v[2], v[3]);
+                            *(u2*)((unsigned short*)a.out + idx) = w2;
+                        } else {
+                            *(f4*)((float*)a.out + idx) = v;
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (e0 + r < a.d && idx + r < a.M) {
+                                if (OUT_BF16) ((unsigned short*)a.out)[idx + r] = (unsigned short)f32_to_bf16_rne(v[r]);
+                                else ((float*)a.out)[idx + r] = v[r];
+                            }
+                    }
+                }
+            }
+            if (more) {
+                f4* Un = Us + ((c + 1) & 1) * CH4;
+#pragma unroll
+                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
+                __syncthreads();
+            }
+        }
+    }
+}
+
+// Upc / Upd for the kernels above; one thread per float, zero where e >= d or comp >= k.
+__global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, int k, int NT, int nchunk)
+{
+    const int b = blockIdx.y;
+    const float* Ub = U + (size_t)b * d * k;
+    const size_t per = (size_t)nchunk * 4 * NT * 64 * 4;   // floats per basis in either copy
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < per; i += (size_t)gridDim.x * blockDim.x) {
+        const int j = (int)(i & 3), lane = (int)((i >> 2) & 63), m = lane & 15, kk = lane >> 4;
+        const size_t hi = i >> 8;
+        const int inner = (int)(hi % NT), outer = (int)((hi / NT) & 3), c = (int)(hi / (4 * NT));
+        {   // compress order: outer = i (load), inner = nt
+            const int e = c * LC + 16 * outer + 4 * kk + j, comp = 16 * inner + m;
+            Upc[(size_t)b * per + i] = (e < d && comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
+        }
+        {   // decompress order: outer = et, inner = w
+            const int e = c * LC + 16 * outer + m, comp = 16 * inner + 4 * kk + j;
+            Upd[(size_t)b * per + i] = (e < d && comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
+        }
+    }
+}
+
+// ======================================================================================
+// host side
+// ======================================================================================
+bool gvq_long_shape(int d, int k) { return d > 128 && k <= 128; }
+int gvq_long_nt(int k) { return k <= 16 ? 1 : k <= 32 ? 2 : k <= 64 ? 4 : k <= 96 ? 6 : 8; }
+int gvq_long_chunks(int d) { return (d + LC - 1) / LC; }
+size_t gvq_long_pack_floats(int d, int k) { return (size_t)gvq_long_chunks(d) * LC * 16 * gvq_long_nt(k); }
+int64_t gvq_long_tiles(int64_t slices) { return (slices + LW_SLICES - 1) / LW_SLICES; }
+
+int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st)
+{
+    const int NT = gvq_long_nt(h->k), nchunk = gvq_long_chunks(h->d);
+    hipLaunchKernelGGL(pack_long_kernel, dim3(64, h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd, h->d, h->k,
+                       NT, nchunk);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+static int64_t tile_of_slice(const gvq_basis* h, int64_t s)
+{
+    if (h->B == 1) return s / LW_SLICES;
+    int lo = 0, hi = h->B;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) / 2;
+        if (h->h_offs[mid] <= s) lo = mid; else hi = mid;
+    }
+    return h->h_ltile[lo] + (s - h->h_offs[lo]) / LW_SLICES;
+}
+
+static LongArgs long_args(const gvq_basis* h, const void* in, void* out, const float* upack, int64_t first_slice,
+                          int64_t n_slices)
+{
+    LongArgs a;
+    a.in = in; a.out = out; a.acc_in = nullptr; a.Upack = (const f4*)upack; a.mu = h->d_mu; a.offs = h->d_offs;
+    a.tstart = h->d_ltile; a.M = h->M; a.S = h->S; a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
+    a.t0 = tile_of_slice(h, a.seg_begin);
+    a.t1 = tile_of_slice(h, a.seg_end - 1) + 1;
+    a.B = h->B; a.d = h->d; a.k = h->k; a.nchunk = gvq_long_chunks(h->d);
+    a.n_workers = 1.f;
+    return a;
+}
+
+template <auto KERN>
+static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
+{
+    const size_t lds = sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * (size_t)a.nchunk * LC;
+    static int per_cu = 0;
+    if (!per_cu) {
+        // the largest slice needs 8 KB NT + 4 KB: allow it once, for every later launch
+        GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * GVQ_MAX_D)));
+        per_cu = 2;
+    }
+    const int64_t tiles = a.t1 - a.t0, cap = (int64_t)h->num_cu * per_cu;
+    const int grid = (int)(tiles < cap ? tiles : cap);
+    hipLaunchKernelGGL(KERN, dim3(grid), dim3(256), lds, st, a);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+template <bool BF16>
+static int compress_long_nt(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
+{
+    switch (NT) {
+    case 1: return launch_long<compress_long_kernel<1, BF16>>(h, a, 1, st);
+    case 2: return launch_long<compress_long_kernel<2, BF16>>(h, a, 2, st);
+    case 4: return launch_long<compress_long_kernel<4, BF16>>(h, a, 4, st);
+    case 6: return launch_long<compress_long_kernel<6, BF16>>(h, a, 6, st);
+    default: return launch_long<compress_long_kernel<8, BF16>>(h, a, 8, st);
+    }
+}
+
+template <bool BF16>
+static int decompress_long_nt(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
+{
+    switch (NT) {
+    case 1: return launch_long<decompress_long_kernel<1, BF16>>(h, a, 1, st);
+    case 2: return launch_long<decompress_long_kernel<2, BF16>>(h, a, 2, st);
+    case 4: return launch_long<decompress_long_kernel<4, BF16>>(h, a, 4, st);
+    case 6: return launch_long<decompress_long_kernel<6, BF16>>(h, a, 6, st);
+    default: return launch_long<decompress_long_kernel<8, BF16>>(h, a, 8, st);
+    }
+}
+
+int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
+                             int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
+{
+    LongArgs a = long_args(h, grad, out, h->d_Upc, first_slice, n_slices);
+    a.acc_in = comp_in;
+    a.n_workers = (float)n_workers;
+    const int NT = gvq_long_nt(h->k);
+    return h->dtype == GVQ_BF16 ? compress_long_nt<true>(h, a, NT, st) : compress_long_nt<false>(h, a, NT, st);
+}
+
+int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
+                               void* out, gvq_dtype_t odt, hipStream_t st)
+{
+    LongArgs a = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
+    const int NT = gvq_long_nt(h->k);
+    return odt == GVQ_BF16 ? decompress_long_nt<true>(h, a, NT, st) : decompress_long_nt<false>(h, a, NT, st);
+}

@@ -17,9 +17,12 @@ struct gvq_basis {
     int64_t* h_offs = nullptr;  // host [B+1]
     int64_t* d_offs = nullptr;  // device [B+1]
     int* d_tile_block = nullptr;  // device [ceil(S/16)]: basis of the first slice of each 16-slice tile (B > 1)
+    int64_t* h_ltile = nullptr; // host [B+1]: first 128-slice tile of each basis (long slices, B > 1)
+    int64_t* d_ltile = nullptr; // device copy
     float* d_U = nullptr;       // [B][d][k]
     float* d_mu = nullptr;      // [B][d]
-    float* d_Upc = nullptr;     // [B][d][KP] U in compress-MFMA operand order (MFMA shapes only)
+    float* d_Upc = nullptr;     // [B][d][KP] U in compress-MFMA operand order (MFMA shapes only; long slices:
+                                // d rounded up to 64, KP = 16 * gvq_long_nt(k))
     float* d_Upd = nullptr;     // [B][d][KP] U in decompress-MFMA operand order
     unsigned short* d_Upb = nullptr;  // [B][d/32][3][NT][64][8] bf16 three-term split of U (bf16 gradients)
     float* d_Umu = nullptr;     // [B][KP] U^T mu (bf16 gradients)
@@ -83,6 +86,14 @@ bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
 // Long slices (d > GVQ_LDS_EIGEN_MAX_D): moments in 64 x 64 blocks, Jacobi out of global memory.
+bool gvq_long_shape(int d, int k);            // codec: LDS-tiled MFMA kernels for d > 128, k <= 128
+size_t gvq_long_pack_floats(int d, int k);    // floats per basis in either operand-order copy of U
+int64_t gvq_long_tiles(int64_t slices);       // 128-slice tiles that cover this many slices of one basis
+int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st);
+int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
+                             int64_t n_slices, const float* comp_in, float* out, hipStream_t st);
+int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
+                               void* out, gvq_dtype_t odt, hipStream_t st);
 int gvq_large_groups(int d);
 size_t gvq_large_partial_doubles(int d, int chunks);   // per basis
 int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipStream_t st);

@@ -26,6 +26,9 @@ CASES = [
     (128 * 1000 + 40, 128, 32, "f32", 0), (128 * 1000 + 40, 128, 16, "bf16", 128 * 77),
     (64 * 700 + 6, 64, 16, "f32", 0), (32 * 900 + 8, 32, 8, "f32", 32 * 100), (16 * 500 + 3, 16, 4, "bf16", 0),
     (24 * 400 + 3, 24, 6, "f32", 24 * 50), (128 * 300 + 5, 128, 7, "f32", 0),
+    # long slices: 128-slice work-group tiles that never straddle two bases
+    (256 * 700 + 40, 256, 32, "f32", 0), (320 * 500 + 9, 320, 40, "bf16", 320 * 130),
+    (192 * 300 + 5, 192, 7, "f32", 192 * 100),
 ]
 
 
