@@ -44,25 +44,30 @@ __device__ __forceinline__ void long_tile(const LongArgs& a, int64_t tile, int& 
 }
 
 // 4 consecutive gradient elements starting at element e of slice s, zero where the slice or the
-// gradient ends (the zero padding of the last slice).
-template <bool BF16>
-__device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s, int e)
+// gradient ends (the zero padding of the last slice).  FAST: the caller guarantees that d is a
+// multiple of 64 and that every slice of the tile lies wholly inside the gradient; the load is
+// then unconditional from `row` (the start of the lane's slice, or of the tile's last slice for
+// lanes past its end, whose results are dropped), which keeps the number of loads in flight
+// known to the compiler, so that it waits for the words it needs and not for the requests
+// behind them.
+template <bool BF16, bool FAST>
+__device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s, const void* row, int e)
 {
     f4 v = {0.f, 0.f, 0.f, 0.f};
-    if (!row_ok || e >= a.d) return v;
-    const int64_t idx = s * a.d + e;
-    if ((a.d & 3) == 0 && idx + 3 < a.M) {
+    if (FAST) {
         if (BF16) {
-            const u2 w = *(const u2*)((const unsigned short*)a.in + idx);
+            const u2 w = *(const u2*)((const unsigned short*)row + e);
             v[0] = __uint_as_float(w.x << 16);
             v[1] = __uint_as_float(w.x & 0xffff0000u);
             v[2] = __uint_as_float(w.y << 16);
             v[3] = __uint_as_float(w.y & 0xffff0000u);
         } else {
-            v = *(const f4*)((const float*)a.in + idx);
+            v = *(const f4*)((const float*)row + e);
         }
         return v;
     }
+    if (!row_ok || e >= a.d) return v;
+    const int64_t idx = s * a.d + e;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
         if (e + r < a.d && idx + r < a.M)
@@ -77,14 +82,117 @@ __device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s,
 // four steps.  Result register r of lane (n, kk) is comp 16nt + 4kk + r of slice n.
 // Upack[b][c][i][nt][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
 // --------------------------------------------------------------------------------------
+template <int NT, bool BF16, bool FAST>
+__device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, const float* mus, const f4* Ub,
+                                                   int64_t first, int64_t end, int64_t lo, int64_t hi)
+{
+    constexpr int CH4 = 4 * NT * 64;              // 128-bit words of one U chunk
+    constexpr int G = NT <= 4 ? NT : (NT == 6 ? 3 : 4);   // comp tiles per group of MFMAs
+    constexpr int NG = NT / G, STEPS = 4 * NG;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_ = lane & 15, kk = lane >> 4;
+
+    int64_t s[2];
+    const void* sc[2];
+    bool ok[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        s[t] = first + wave * 32 + 16 * t + n_;
+        ok[t] = s[t] >= lo && s[t] < hi;
+        const int64_t row = (s[t] < end ? s[t] : end - 1) * a.d;
+        sc[t] = BF16 ? (const void*)((const unsigned short*)a.in + row) : (const void*)((const float*)a.in + row);
+    }
+    f4 acc[2][NT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[t][nt] = f4{0.f, 0.f, 0.f, 0.f};
+    // a word of x is requested again, for the next chunk, as soon as the MFMAs of its last use
+    // are issued, so the load has most of a chunk's MFMA time to arrive.  All requests are
+    // unconditional (in the last chunk the same words are simply fetched again).
+    const int last = a.nchunk - 1;
+    f4 xr[2][4], ur[NT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], 16 * i + 4 * kk);
+
+    for (int c = 0; c < a.nchunk; ++c) {
+        const int cn = c < last ? c + 1 : last;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)cn * CH4 + tid + 256 * q];
+        const f4* Uc = Us + (c & 1) * CH4;
+        const float* mc = mus + c * LC + 4 * kk;
+        // MFMA steps (i, g): the LDS operands of step st + 1 are requested before the MFMAs of
+        // step st are issued; inside a step the accumulators are innermost, 2 G independent
+        // chains between two uses of one
+        f4 uw[2][G], mw[2];
+#pragma unroll
+        for (int q = 0; q < G; ++q) uw[0][q] = Uc[q * 64 + lane];
+        mw[0] = *(const f4*)mc;
+        __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            const int i = st / NG, g = st % NG;
+            if (st + 1 < STEPS) {
+                const int i1 = (st + 1) / NG, g1 = (st + 1) % NG;
+#pragma unroll
+                for (int q = 0; q < G; ++q) uw[(st + 1) & 1][q] = Uc[(i1 * NT + g1 * G + q) * 64 + lane];
+                if (g1 == 0) mw[i1 & 1] = *(const f4*)(mc + 16 * i1);
+            }
+            const f4 x0 = xr[0][i] - mw[i & 1], x1 = xr[1][i] - mw[i & 1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < G; ++q) {
+                    const int nt = g * G + q;
+                    acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[st & 1][q][j], x0[j], acc[0][nt], 0, 0, 0);
+                    acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[st & 1][q][j], x1[j], acc[1][nt], 0, 0, 0);
+                }
+            if (g == NG - 1) {   // word i is used up
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 16 * i + 4 * kk);
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        if (c < last) {
+            f4* Un = Us + ((c + 1) & 1) * CH4;   // last read one chunk ago, before the previous barrier
+#pragma unroll
+            for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
+            __syncthreads();
+        }
+    }
+
+    float* Y = (float*)a.out;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        if (!ok[t]) continue;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int c0 = 16 * nt + 4 * kk;
+            if (c0 >= a.k) continue;
+            const int64_t o = s[t] * a.k + c0;
+            f4 v = acc[t][nt];
+            if ((a.k & 3) == 0) {
+                if (a.acc_in) v += *(const f4*)(a.acc_in + o);
+                *(f4*)(Y + o) = v;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
+            }
+        }
+    }
+}
+
 template <int NT, bool BF16>
 __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
 {
     extern __shared__ f4 smem[];
-    constexpr int CH4 = 4 * NT * 64;              // 128-bit words of one U chunk
+    constexpr int CH4 = 4 * NT * 64;
     f4* Us = smem;                                // [2][CH4]
     float* mus = (float*)(smem + 2 * CH4);        // [nchunk * LC]  mu / N, zero past d
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_ = lane & 15, kk = lane >> 4;
+    const int tid = threadIdx.x;
 
     for (int64_t tile = a.t0 + blockIdx.x; tile < a.t1; tile += gridDim.x) {
         int b;
@@ -95,89 +203,13 @@ __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
         __syncthreads();   // the previous tile's readers are done with mus and Us
         for (int e = tid; e < a.nchunk * LC; e += 256)
             mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] / a.n_workers : 0.f;
-        f4 ur[NT];
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
         __syncthreads();
-
-        int64_t s[2];
-        bool ok[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            s[t] = first + wave * 32 + 16 * t + n_;
-            ok[t] = s[t] >= lo && s[t] < hi;
-        }
-        f4 acc[2][NT];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[t][nt] = f4{0.f, 0.f, 0.f, 0.f};
-        f4 xr[2][4], xn[2][4];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16>(a, ok[t], s[t], 16 * i + 4 * kk);
-
-        for (int c = 0; c < a.nchunk; ++c) {
-            const bool more = c + 1 < a.nchunk;
-            if (more) {
-#pragma unroll
-                for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)(c + 1) * CH4 + tid + 256 * q];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        xn[t][i] = load_x4<BF16>(a, ok[t], s[t], (c + 1) * LC + 16 * i + 4 * kk);
-            }
-            const f4* Uc = Us + (c & 1) * CH4;
-            __builtin_amdgcn_s_setprio(3);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const f4 mw = *(const f4*)(mus + c * LC + 16 * i + 4 * kk);
-                const f4 x0 = xr[0][i] - mw, x1 = xr[1][i] - mw;
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const f4 uw = Uc[(i * NT + nt) * 64 + lane];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        acc[0][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], x0[j], acc[0][nt], 0, 0, 0);
-                        acc[1][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], x1[j], acc[1][nt], 0, 0, 0);
-                    }
-                }
-            }
-            __builtin_amdgcn_s_setprio(0);
-            if (more) {
-                f4* Un = Us + ((c + 1) & 1) * CH4;   // last read one chunk ago, before the previous barrier
-#pragma unroll
-                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) xr[t][i] = xn[t][i];
-                __syncthreads();
-            }
-        }
-
-        float* Y = (float*)a.out;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            if (!ok[t]) continue;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int c0 = 16 * nt + 4 * kk;
-                if (c0 >= a.k) continue;
-                const int64_t o = s[t] * a.k + c0;
-                f4 v = acc[t][nt];
-                if ((a.k & 3) == 0) {
-                    if (a.acc_in) v += *(const f4*)(a.acc_in + o);
-                    *(f4*)(Y + o) = v;
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
-                }
-            }
-        }
+        if ((a.d & 63) == 0 && end * a.d <= a.M)
+            compress_long_tile<NT, BF16, true>(a, Us, mus, Ub, first, end, lo, hi);
+        else
+            compress_long_tile<NT, BF16, false>(a, Us, mus, Ub, first, end, lo, hi);
     }
 }
 
@@ -234,32 +266,46 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
                 }
             }
         }
+        const bool vec = (a.d & 3) == 0 && end * a.d <= a.M;   // every store of the tile is a whole word
 
         for (int c = 0; c < a.nchunk; ++c) {
-            const bool more = c + 1 < a.nchunk;
-            if (more) {
+            const int cn = c + 1 < a.nchunk ? c + 1 : c;   // unconditional: the last chunk is fetched twice
 #pragma unroll
-                for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)(c + 1) * CH4 + tid + 256 * q];
-            }
+            for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)cn * CH4 + tid + 256 * q];
             const f4* Uc = Us + (c & 1) * CH4;
             f4 acc[2][4];
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int et = 0; et < 4; ++et) acc[t][et] = f4{0.f, 0.f, 0.f, 0.f};
+            // comp group w + 1's operands are requested before the MFMAs of group w; the 8
+            // accumulators are innermost
+            f4 uw[2][4];
+#pragma unroll
+            for (int et = 0; et < 4; ++et) uw[0][et] = Uc[(et * NT) * 64 + lane];
             __builtin_amdgcn_s_setprio(3);
 #pragma unroll
-            for (int et = 0; et < 4; ++et)
+            for (int w = 0; w < NT; ++w) {
+                if (w + 1 < NT) {
 #pragma unroll
-                for (int w = 0; w < NT; ++w) {
-                    const f4 uw = Uc[(et * NT + w) * 64 + lane];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        acc[0][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], yr[0][w][j], acc[0][et], 0, 0, 0);
-                        acc[1][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[j], yr[1][w][j], acc[1][et], 0, 0, 0);
-                    }
+                    for (int et = 0; et < 4; ++et) uw[(w + 1) & 1][et] = Uc[(et * NT + w + 1) * 64 + lane];
                 }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int et = 0; et < 4; ++et) {
+                        acc[0][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[w & 1][et][j], yr[0][w][j], acc[0][et], 0, 0, 0);
+                        acc[1][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[w & 1][et][j], yr[1][w][j], acc[1][et], 0, 0, 0);
+                    }
+            }
             __builtin_amdgcn_s_setprio(0);
+            // the next U chunk goes to LDS before this chunk's stores are issued, so that waiting
+            // for its loads does not wait for the stores
+            if (c + 1 < a.nchunk) {
+                f4* Un = Us + ((c + 1) & 1) * CH4;
+#pragma unroll
+                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
+            }
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 if (!ok[t]) continue;
@@ -269,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
                     if (e0 >= a.d) continue;
                     const f4 v = acc[t][et] + *(const f4*)(mus + e0);
                     const int64_t idx = s[t] * a.d + e0;
-                    if ((a.d & 3) == 0 && idx + 3 < a.M) {
+                    if (vec) {
                         if (OUT_BF16) {
                             u2 w2;
                             w2.x = pack_bf16x2(v[0], v[1]);
@@ -288,12 +334,7 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
                     }
                 }
             }
-            if (more) {
-                f4* Un = Us + ((c + 1) & 1) * CH4;
-#pragma unroll
-                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
-                __syncthreads();
-            }
+            if (c + 1 < a.nchunk) __syncthreads();
         }
     }
 }
@@ -365,12 +406,17 @@ template <auto KERN>
 static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
 {
     const size_t lds = sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * (size_t)a.nchunk * LC;
-    static int per_cu = 0;
-    if (!per_cu) {
+    static bool attr_set = false;
+    if (!attr_set) {
         // the largest slice needs 8 KB NT + 4 KB: allow it once, for every later launch
         GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * GVQ_MAX_D)));
-        per_cu = 2;
+        attr_set = true;
+    }
+    int per_cu = gvq_opt_wg_per_cu();
+    if (per_cu <= 0) {
+        GVQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)KERN, 256, lds));
+        if (per_cu < 1) per_cu = 1;
     }
     const int64_t tiles = a.t1 - a.t0, cap = (int64_t)h->num_cu * per_cu;
     const int grid = (int)(tiles < cap ? tiles : cap);
