@@ -367,56 +367,25 @@ __device__ double block_sum(double v, double* red)
     return tot;
 }
 
-__global__ void eigen_kernel(EigArgs a)
+// The sweeps of the parallel-order Jacobi on the n x n matrix A in LDS (n even), V <- V J in
+// global memory (n x n, row-major), all threads of the work-group.  fro2 = squared Frobenius
+// norm of A.  Returns the number of sweeps used, -1 if the off-diagonal mass did not fall below
+// tol^2 fro2 within max_sweeps (or turned NaN).
+__device__ __forceinline__ int jacobi_lds_sweeps(double* A, double* V, int n, double* cs, double* sn, double* red, int* pp, int* qq,
+                                 double fro2, int max_sweeps, double tol)
 {
-    extern __shared__ double smem[];
-    const int d = a.d, n = d + (d & 1), half = n >> 1;
-    double* A = smem;                       // [n][n]
-    double* cs = A + n * n;                 // [half]
-    double* sn = cs + half;                 // [half]
-    double* red = sn + half;                // [32]
-    double* lam = red + 32;                 // [n]
-    int* pp = (int*)(lam + n);              // [half]
-    int* qq = pp + half;                    // [half]
-    int* order = qq + half;                 // [n]
-    const int b = blockIdx.x, tid = threadIdx.x, nth = blockDim.x;
-
-    const int W = d * d + d;
-    const double* mom = a.mom + (size_t)b * W;
-    const int64_t full = a.M / d;
-    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
-    const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
-
-    double* V = a.V + (size_t)b * n * n;
-    double* cov = a.cov + (size_t)b * d * d;
-    double fro2 = 0.0;
-    for (int i = tid; i < n * n; i += nth) {
-        int r = i / n, c = i - r * n;
-        double v = 0.0;
-        if (r < d && c < d) {
-            // upper and lower halves of the Gram sum are bit-identical (same products, same order)
-            // true divisions: a constant gradient then gives exactly C = 0
-            v = ns > 0.0 ? mom[r * d + c] / ns - (mom[d * d + r] / ns) * (mom[d * d + c] / ns) : 0.0;
-            cov[r * d + c] = v;
-        }
-        A[i] = v;
-        V[i] = r == c ? 1.0 : 0.0;
-        fro2 += v * v;
-    }
-    for (int i = tid; i < d; i += nth) a.mu[(size_t)b * d + i] = ns > 0.0 ? (float)(mom[d * d + i] / ns) : 0.0f;
-    fro2 = block_sum(fro2, red);
-
+    const int half = n >> 1, tid = threadIdx.x, nth = blockDim.x;
     int sweeps_used = -1;
-    for (int sweep = 0; sweep <= a.max_sweeps; ++sweep) {
+    for (int sweep = 0; sweep <= max_sweeps; ++sweep) {
         double off2 = 0.0;
         for (int i = tid; i < n * n; i += nth) {
             int r = i / n, c = i - r * n;
             if (r != c) off2 += A[i] * A[i];
         }
         off2 = block_sum(off2, red);
-        if (!(off2 > a.tol * a.tol * fro2)) { sweeps_used = sweep; break; }
+        if (!(off2 > tol * tol * fro2)) { sweeps_used = sweep; break; }
         if (off2 != off2) break;  // NaN: give up
-        if (sweep == a.max_sweeps) break;
+        if (sweep == max_sweeps) break;
 
         for (int round = 0; round < n - 1; ++round) {
             if (tid < half) {
@@ -474,6 +443,49 @@ __global__ void eigen_kernel(EigArgs a)
             __syncthreads();
         }
     }
+    return sweeps_used;
+}
+
+__global__ void eigen_kernel(EigArgs a)
+{
+    extern __shared__ double smem[];
+    const int d = a.d, n = d + (d & 1), half = n >> 1;
+    double* A = smem;                       // [n][n]
+    double* cs = A + n * n;                 // [half]
+    double* sn = cs + half;                 // [half]
+    double* red = sn + half;                // [32]
+    double* lam = red + 32;                 // [n]
+    int* pp = (int*)(lam + n);              // [half]
+    int* qq = pp + half;                    // [half]
+    int* order = qq + half;                 // [n]
+    const int b = blockIdx.x, tid = threadIdx.x, nth = blockDim.x;
+
+    const int W = d * d + d;
+    const double* mom = a.mom + (size_t)b * W;
+    const int64_t full = a.M / d;
+    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
+    const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
+
+    double* V = a.V + (size_t)b * n * n;
+    double* cov = a.cov + (size_t)b * d * d;
+    double fro2 = 0.0;
+    for (int i = tid; i < n * n; i += nth) {
+        int r = i / n, c = i - r * n;
+        double v = 0.0;
+        if (r < d && c < d) {
+            // upper and lower halves of the Gram sum are bit-identical (same products, same order)
+            // true divisions: a constant gradient then gives exactly C = 0
+            v = ns > 0.0 ? mom[r * d + c] / ns - (mom[d * d + r] / ns) * (mom[d * d + c] / ns) : 0.0;
+            cov[r * d + c] = v;
+        }
+        A[i] = v;
+        V[i] = r == c ? 1.0 : 0.0;
+        fro2 += v * v;
+    }
+    for (int i = tid; i < d; i += nth) a.mu[(size_t)b * d + i] = ns > 0.0 ? (float)(mom[d * d + i] / ns) : 0.0f;
+    fro2 = block_sum(fro2, red);
+
+    const int sweeps_used = jacobi_lds_sweeps(A, V, n, cs, sn, red, pp, qq, fro2, a.max_sweeps, a.tol);
 
     // eigenvalues in decreasing order (ties: lower index first)
     for (int i = tid; i < d; i += nth) lam[i] = A[i * n + i];
@@ -503,6 +515,190 @@ __global__ void eigen_kernel(EigArgs a)
         for (int e = 0; e < d; ++e) a.U[((size_t)b * d + e) * a.k + i] = (float)(sign * V[e * n + col]);
     }
     if (tid == 0) a.sweeps[b] = sweeps_used;
+}
+
+// --------------------------------------------------------------------------------------
+// First-slice sampling with fewer samples than dimensions (Section 3: L time samples of one slice,
+// slice sizes in the hundreds).  The covariance C = Xc^T Xc / L (Xc: the L centred samples as
+// rows) has rank < L, and its non-zero eigenpairs are those of the small L x L matrix
+// K = Xc Xc^T / L: K v = lambda v  =>  C (Xc^T v) = lambda (Xc^T v).  So the Jacobi runs on K in
+// LDS whatever d is, and the kept directions are u_i = Xc^T v_i, normalised and cleaned with one
+// round of Gram-Schmidt against the columns before them.  Directions beyond the rank of the data
+// (eigenvalue <= 1e-12 of the largest) are not determined by it; they are completed with unit
+// vectors made orthogonal to the columns so far, so that U always has orthonormal columns.
+// One work-group per basis.  work[b]: [m*m] eigenvectors of K, then [k][d] the columns of U in
+// float64.
+// --------------------------------------------------------------------------------------
+#define GVQ_GRAM_MAX_L 128
+#define GVQ_GRAM_MAX_K 256
+struct GramArgs {
+    gvq_ptrs grads[GVQ_GRAM_MAX_L / GVQ_MAX_PTRS];
+    int L;
+    const double* mom;     // [B][d*d+d] from first_slice_moments_kernel
+    const int64_t* offs;
+    int64_t M;
+    int d, k, bf16;
+    double* cov;           // [B][d][d]
+    double* work;          // [B][work_stride]
+    size_t work_stride;
+    double* eig;           // [B][d]
+    float* U;              // [B][d][k]
+    float* mu;             // [B][d]
+    int* sweeps;           // [B]
+    int max_sweeps;
+    double tol;
+};
+
+size_t gvq_gram_lds_bytes(int L, int k)
+{
+    const int m = L + (L & 1), half = m / 2;
+    return sizeof(double) * ((size_t)m * m + 2 * half + 32 + m + k) + sizeof(int) * (2 * half + m);
+}
+
+__global__ __launch_bounds__(1024) void gram_eigen_kernel(GramArgs a)
+{
+    extern __shared__ double smem[];
+    const int d = a.d, k = a.k, L = a.L, m = L + (L & 1), half = m >> 1;
+    double* A = smem;                       // [m][m]
+    double* cs = A + m * m;                 // [half]
+    double* sn = cs + half;                 // [half]
+    double* red = sn + half;                // [32]
+    double* lam = red + 32;                 // [m]
+    double* dots = lam + m;                 // [k]
+    int* pp = (int*)(dots + k);             // [half]
+    int* qq = pp + half;                    // [half]
+    int* order = qq + half;                 // [m]
+    const int b = blockIdx.x, tid = threadIdx.x, nth = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nth >> 6;
+
+    const double* mom = a.mom + (size_t)b * ((size_t)d * d + d);
+    double* cov = a.cov + (size_t)b * d * d;
+    double* V = a.work + (size_t)b * a.work_stride;   // [m][m]
+    double* Uw = V + (size_t)m * m;                   // [k][d]
+    const int64_t j = a.offs[b];
+    if ((j + 1) * d > a.M) {
+        // no full first slice: the trivial basis, as in the general solver
+        for (int i = tid; i < d * d; i += nth) cov[i] = 0.0;
+        for (int i = tid; i < d; i += nth) { a.mu[(size_t)b * d + i] = 0.f; a.eig[(size_t)b * d + i] = 0.0; }
+        for (int i = tid; i < d * k; i += nth) a.U[(size_t)b * d * k + i] = (i / k == i % k) ? 1.f : 0.f;
+        if (tid == 0) a.sweeps[b] = 0;
+        return;
+    }
+    const double ns = (double)L;
+    for (int i = tid; i < d * d; i += nth) {
+        const int r = i / d, c = i - r * d;
+        cov[i] = mom[i] / ns - (mom[(size_t)d * d + r] / ns) * (mom[(size_t)d * d + c] / ns);
+    }
+    for (int i = tid; i < d; i += nth) a.mu[(size_t)b * d + i] = (float)(mom[(size_t)d * d + i] / ns);
+    auto xc = [&](int l, int e) {   // centred sample l, element e
+        return (double)load_elem(a.grads[l / GVQ_MAX_PTRS].p[l % GVQ_MAX_PTRS], a.bf16 != 0, j * d + e) -
+               mom[(size_t)d * d + e] / ns;
+    };
+    // K (upper triangle computed, mirrored), zero row/column for the padding index
+    for (int i = tid; i < m * m; i += nth) {
+        const int r = i / m, c = i - r * m;
+        if (r > c) continue;
+        double v = 0.0;
+        if (c < L) {
+            for (int e = 0; e < d; ++e) v = fma(xc(r, e), xc(c, e), v);
+            v /= ns;
+        }
+        A[r * m + c] = v;
+        A[c * m + r] = v;
+    }
+    for (int i = tid; i < m * m; i += nth) V[i] = (i / m == i % m) ? 1.0 : 0.0;
+    __syncthreads();
+    double fro2 = 0.0;
+    for (int i = tid; i < m * m; i += nth) fro2 += A[i] * A[i];
+    fro2 = block_sum(fro2, red);
+    const int sweeps_used = jacobi_lds_sweeps(A, V, m, cs, sn, red, pp, qq, fro2, a.max_sweeps, a.tol);
+    __syncthreads();
+
+    // eigenvalues of K in decreasing order (ties: lower index first, NaN last)
+    // K is positive semi-definite: a negative eigenvalue is rounding noise around zero
+    for (int i = tid; i < L; i += nth) lam[i] = A[i * m + i] < 0.0 ? 0.0 : A[i * m + i];
+    __syncthreads();
+    for (int i = tid; i < L; i += nth) {
+        const double li = lam[i] == lam[i] ? lam[i] : -INFINITY;
+        int rank = 0;
+        for (int q = 0; q < L; ++q) {
+            const double lq = lam[q] == lam[q] ? lam[q] : -INFINITY;
+            if (lq > li || (lq == li && q < i)) ++rank;
+        }
+        order[rank] = i;
+    }
+    __syncthreads();
+    for (int i = tid; i < d; i += nth) a.eig[(size_t)b * d + i] = i < L ? lam[order[i]] : 0.0;
+    const double top = lam[order[0]];
+
+    // raw directions Xc^T v_i for the columns the data determines, zero for the others
+    for (int i = tid; i < k * d; i += nth) {
+        const int col = i / d, e = i - col * d;
+        double v = 0.0;
+        if (col < L && lam[order[col]] > 1e-12 * top) {
+            const int vc = order[col];
+            for (int l = 0; l < L; ++l) v = fma(V[l * m + vc], xc(l, e), v);
+        }
+        Uw[i] = v;
+    }
+    __syncthreads();
+
+    // columns one after the other: orthogonalise against the earlier ones (twice), normalise
+    int next_unit = 0;
+    for (int col = 0; col < k; ++col) {
+        double* w = Uw + (size_t)col * d;
+        const bool determined = col < L && lam[order[col]] > 1e-12 * top;   // uniform
+        for (int attempt = 0;; ++attempt) {
+            if (!determined) {
+                for (int e = tid; e < d; e += nth) w[e] = e == next_unit ? 1.0 : 0.0;
+                ++next_unit;
+                __syncthreads();
+            }
+            for (int pass = 0; pass < 2; ++pass) {
+                for (int q = wave; q < col; q += nw) {
+                    const double* u = Uw + (size_t)q * d;
+                    double acc = 0.0;
+                    for (int e = lane; e < d; e += 64) acc = fma(u[e], w[e], acc);
+                    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                    if (lane == 0) dots[q] = acc;
+                }
+                __syncthreads();
+                for (int e = tid; e < d; e += nth) {
+                    double v = w[e];
+                    for (int q = 0; q < col; ++q) v = fma(-dots[q], Uw[(size_t)q * d + e], v);
+                    w[e] = v;
+                }
+                __syncthreads();
+            }
+            double n2 = 0.0;
+            for (int e = tid; e < d; e += nth) n2 += w[e] * w[e];
+            n2 = block_sum(n2, red);
+            // a unit vector that lies almost inside the span so far is a poor start: take the next one
+            if (!determined && n2 < 0.25 && next_unit < d) continue;
+            const double inv = n2 > 0.0 ? 1.0 / sqrt(n2) : 0.0;
+            for (int e = tid; e < d; e += nth) w[e] *= inv;
+            __syncthreads();
+            break;
+        }
+    }
+    // sign: largest-magnitude entry (lowest index on ties) positive
+    for (int col = tid; col < k; col += nth) {
+        const double* w = Uw + (size_t)col * d;
+        int arg = 0;
+        double big = -1.0;
+        for (int e = 0; e < d; ++e) {
+            const double mag = fabs(w[e]);
+            if (mag > big) { big = mag; arg = e; }
+        }
+        const double sign = w[arg] < 0.0 ? -1.0 : 1.0;
+        for (int e = 0; e < d; ++e) a.U[((size_t)b * d + e) * k + col] = (float)(sign * w[e]);
+    }
+    if (tid == 0) a.sweeps[b] = sweeps_used;
+}
+
+// The small-matrix route is taken when it applies and its scratch fits the eigenvector work space.
+bool gvq_gram_shape(int d, int k, int L)
+{
+    return L >= 2 && L <= GVQ_GRAM_MAX_L && 2 * L <= d && k <= GVQ_GRAM_MAX_K && 4 * (int64_t)k <= 3 * (int64_t)d;
 }
 
 // Section 3, "compressor reuse": moments of the first slice of every basis only -- L samples of d
@@ -649,6 +845,23 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         GVQ_HIP(hipGetLastError());
     }
 
+    if (first_slice_only && gvq_gram_shape(d, h->k, L)) {
+        GramArgs g;
+        for (int l = 0; l < L; ++l) g.grads[l / GVQ_MAX_PTRS].p[l % GVQ_MAX_PTRS] = grads[l];
+        g.L = L; g.mom = h->d_mom; g.offs = h->d_offs; g.M = h->M; g.d = d; g.k = h->k;
+        g.bf16 = h->dtype == GVQ_BF16 ? 1 : 0;
+        g.cov = h->d_cov; g.work = h->d_V; g.work_stride = (size_t)(d + (d & 1)) * (d + (d & 1));
+        g.eig = h->d_eig; g.U = h->d_U; g.mu = h->d_mu; g.sweeps = h->d_sweeps; g.max_sweeps = 60; g.tol = 1e-15;
+        static bool gram_attr_set = false;
+        if (!gram_attr_set) {
+            GVQ_HIP(hipFuncSetAttribute((const void*)gram_eigen_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)gvq_gram_lds_bytes(GVQ_GRAM_MAX_L, GVQ_GRAM_MAX_K)));
+            gram_attr_set = true;
+        }
+        hipLaunchKernelGGL(gram_eigen_kernel, dim3(h->B), dim3(1024), gvq_gram_lds_bytes(L, h->k), st, g);
+        GVQ_HIP(hipGetLastError());
+        return gvq_launch_pack(h, st);
+    }
     if (d > GVQ_LDS_EIGEN_MAX_D) {
         const int rc = gvq_launch_eigen_large(h, L, first_slice_only, st);
         return rc != GVQ_OK ? rc : gvq_launch_pack(h, st);

@@ -45,6 +45,10 @@ def _check_fit(w, first_slice_only=False, mean_offset=None, angle_rank=None):
         Ub = U[bb].astype(np.float64)
         assert np.max(np.abs(Ub.T @ Ub - np.eye(w.k))) < 1e-5
         kk = w.k if angle_rank is None else angle_rank
+        if first_slice_only:
+            kk = min(kk, w.L - 1)            # what L samples determine
+            while kk > 1 and eigo[bb][kk - 1] - eigo[bb][kk] < 1e-6 * lam1:
+                kk -= 1
         assert max_angle(Ub[:, :kk], Uo[bb][:, :kk]) < ANGLE_TOL
         for i in range(w.k):
             assert Ub[np.argmax(np.abs(Ub[:, i])), i] > 0
@@ -80,6 +84,30 @@ def test_fit_parity_first_slice_of_a_768_element_slice():
     dimensions, so the covariance has rank L - 1 and the kept components span its range."""
     w = _wl(768 * 40 + 100, 768, 16, 2, 24, rank=6, sigma=0.1)
     _check_fit(w, first_slice_only=True)
+
+
+@pytest.mark.parametrize("M,d,k,L,dtype,block_elems", [
+    (256 * 30 + 7, 256, 40, 24, "f32", 0),             # more columns than the samples determine
+    (256 * 64, 256, 40, 100, "bf16", 256 * 16),        # a 100 x 100 sample matrix, four bases
+    (130 * 9 + 1, 130, 7, 65, "f32", 0),               # as many samples as the small-matrix route takes
+    (130 * 9 + 1, 130, 7, 66, "f32", 0),               # one more: the general solver
+    (192 * 8, 192, 150, 12, "f32", 0),                 # too many columns for it: the general solver
+])
+def test_fit_parity_first_slice_few_samples(M, d, k, L, dtype, block_elems):
+    _check_fit(_wl(M, d, k, 2, L, dtype=dtype, rank=5, sigma=0.2, block_elems=block_elems), first_slice_only=True)
+
+
+def test_fit_first_slice_of_identical_samples_gives_unit_vectors():
+    M, d, k = 256 * 10, 256, 8
+    g = torch.randn(M, generator=torch.Generator().manual_seed(9))
+    b = gvq.Basis(M, d, k)
+    b.fit([g.to(DEV)] * 6, first_slice_only=True)
+    assert b.fit_status() == 0
+    U, mu, eig = b.export()
+    b.close()
+    assert np.all(eig == 0)
+    np.testing.assert_array_equal(mu[0], g[:d].numpy())
+    np.testing.assert_array_equal(U[0], np.eye(d, k, dtype=np.float32))
 
 
 def test_fit_is_bitwise_reproducible():
