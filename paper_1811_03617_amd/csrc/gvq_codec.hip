@@ -1116,7 +1116,9 @@ int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, d
     a.Upack2 = (const f4*)h->d_Upd;
     const bool bf = h->dtype == GVQ_BF16;
     int rc = GVQ_OK;
-    if (gvq_mfma_shape(h->d, h->k)) {
+    if (gvq_long_shape(h->d, h->k)) {
+        rc = gvq_launch_loss_long(h, grad, n_workers, h->d_loss_slice, st);
+    } else if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
         case 16: rc = bf ? launch_loss_d<16, true>(h, a, st) : launch_loss_d<16, false>(h, a, st); break;
         case 32: rc = bf ? launch_loss_d<32, true>(h, a, st) : launch_loss_d<32, false>(h, a, st); break;

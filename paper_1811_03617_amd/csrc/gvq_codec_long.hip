@@ -17,6 +17,7 @@ struct LongArgs {
     void* out;
     const float* acc_in;     // compress only, may be null
     const f4* Upack;         // [B][nchunk][4][NT][64] f4 in the kernel's operand order
+    const f4* Upack2;        // loss kernel only: the decompress-order copy
     const float* mu;         // [B][d]
     const int64_t* offs;     // [B+1]
     const int64_t* tstart;   // [B+1] first tile of each basis (B > 1 only)
@@ -82,9 +83,9 @@ __device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s,
 // four steps.  Result register r of lane (n, kk) is comp 16nt + 4kk + r of slice n.
 // Upack[b][c][i][nt][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
 // --------------------------------------------------------------------------------------
-template <int NT, bool BF16, bool FAST>
+template <int NT, bool BF16, bool FAST, bool LOSS>
 __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, const float* mus, const f4* Ub,
-                                                   int64_t first, int64_t end, int64_t lo, int64_t hi)
+                                                   const f4* Ub2, int64_t first, int64_t end, int64_t lo, int64_t hi)
 {
     constexpr int CH4 = 4 * NT * 64;              // 128-bit words of one U chunk
     constexpr int G = NT <= 4 ? NT : (NT == 6 ? 3 : 4);   // comp tiles per group of MFMAs
@@ -163,6 +164,82 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
         }
     }
 
+    if constexpr (LOSS) {
+        // Eq. (6): the residual (x - mu/N) - U y of the same tile.  The accumulators already are
+        // the B operand of the reconstruction product (lane (n, kk) holds comps 16w + 4kk + j of
+        // slice n), and the product's result registers cover the same elements as the x words
+        // of the projection (element tile et <-> word i), so x is simply read once more, chunk by
+        // chunk, and nothing but the squared sum leaves the registers.
+        __syncthreads();   // every wave is done with the projection's last U chunk
+#pragma unroll
+        for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub2[tid + 256 * q];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], 16 * i + 4 * kk);
+        __syncthreads();
+        float sq[2] = {0.f, 0.f};
+        for (int c = 0; c < a.nchunk; ++c) {
+            const int cn = c < last ? c + 1 : last;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) ur[q] = Ub2[(size_t)cn * CH4 + tid + 256 * q];
+            const f4* Uc = Us + (c & 1) * CH4;
+            f4 rec[2][4];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int et = 0; et < 4; ++et) rec[t][et] = f4{0.f, 0.f, 0.f, 0.f};
+            f4 uw[2][4];
+#pragma unroll
+            for (int et = 0; et < 4; ++et) uw[0][et] = Uc[(et * NT) * 64 + lane];
+            __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+            for (int w = 0; w < NT; ++w) {
+                if (w + 1 < NT) {
+#pragma unroll
+                    for (int et = 0; et < 4; ++et) uw[(w + 1) & 1][et] = Uc[(et * NT + w + 1) * 64 + lane];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int et = 0; et < 4; ++et) {
+                        rec[0][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[w & 1][et][j], acc[0][w][j], rec[0][et], 0, 0, 0);
+                        rec[1][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uw[w & 1][et][j], acc[1][w][j], rec[1][et], 0, 0, 0);
+                    }
+            }
+            __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+            for (int et = 0; et < 4; ++et) {
+                const int e0 = c * LC + 16 * et + 4 * kk;
+                const f4 mw = *(const f4*)(mus + e0);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const f4 res = (xr[t][et] - mw) - rec[t][et];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // only elements that exist count (not the zero padding of the last slice)
+                        const bool real = FAST ? true : (e0 + r < a.d && s[t] * a.d + e0 + r < a.M);
+                        if (real) sq[t] = fmaf(res[r], res[r], sq[t]);
+                    }
+                    xr[t][et] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 16 * et + 4 * kk);
+                }
+            }
+            if (c < last) {
+                f4* Un = Us + ((c + 1) & 1) * CH4;
+#pragma unroll
+                for (int q = 0; q < NT; ++q) Un[tid + 256 * q] = ur[q];
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float v = sq[t];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (kk == 0 && ok[t]) ((float*)a.out)[s[t]] = v;
+        }
+        return;
+    }
     float* Y = (float*)a.out;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -185,7 +262,7 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
     }
 }
 
-template <int NT, bool BF16>
+template <int NT, bool BF16, bool LOSS>
 __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
 {
     extern __shared__ f4 smem[];
@@ -206,10 +283,11 @@ __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
         __syncthreads();
+        const f4* Ub2 = LOSS ? a.Upack2 + (size_t)b * a.nchunk * CH4 : nullptr;
         if ((a.d & 63) == 0 && end * a.d <= a.M)
-            compress_long_tile<NT, BF16, true>(a, Us, mus, Ub, first, end, lo, hi);
+            compress_long_tile<NT, BF16, true, LOSS>(a, Us, mus, Ub, Ub2, first, end, lo, hi);
         else
-            compress_long_tile<NT, BF16, false>(a, Us, mus, Ub, first, end, lo, hi);
+            compress_long_tile<NT, BF16, false, LOSS>(a, Us, mus, Ub, Ub2, first, end, lo, hi);
     }
 }
 
@@ -393,7 +471,7 @@ static LongArgs long_args(const gvq_basis* h, const void* in, void* out, const f
                           int64_t n_slices)
 {
     LongArgs a;
-    a.in = in; a.out = out; a.acc_in = nullptr; a.Upack = (const f4*)upack; a.mu = h->d_mu; a.offs = h->d_offs;
+    a.in = in; a.out = out; a.acc_in = nullptr; a.Upack = (const f4*)upack; a.Upack2 = nullptr; a.mu = h->d_mu; a.offs = h->d_offs;
     a.tstart = h->d_ltile; a.M = h->M; a.S = h->S; a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
     a.t0 = tile_of_slice(h, a.seg_begin);
     a.t1 = tile_of_slice(h, a.seg_end - 1) + 1;
@@ -425,15 +503,15 @@ static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_
     return GVQ_OK;
 }
 
-template <bool BF16>
+template <bool BF16, bool LOSS>
 static int compress_long_nt(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
 {
     switch (NT) {
-    case 1: return launch_long<compress_long_kernel<1, BF16>>(h, a, 1, st);
-    case 2: return launch_long<compress_long_kernel<2, BF16>>(h, a, 2, st);
-    case 4: return launch_long<compress_long_kernel<4, BF16>>(h, a, 4, st);
-    case 6: return launch_long<compress_long_kernel<6, BF16>>(h, a, 6, st);
-    default: return launch_long<compress_long_kernel<8, BF16>>(h, a, 8, st);
+    case 1: return launch_long<compress_long_kernel<1, BF16, LOSS>>(h, a, 1, st);
+    case 2: return launch_long<compress_long_kernel<2, BF16, LOSS>>(h, a, 2, st);
+    case 4: return launch_long<compress_long_kernel<4, BF16, LOSS>>(h, a, 4, st);
+    case 6: return launch_long<compress_long_kernel<6, BF16, LOSS>>(h, a, 6, st);
+    default: return launch_long<compress_long_kernel<8, BF16, LOSS>>(h, a, 8, st);
     }
 }
 
@@ -456,7 +534,19 @@ int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers
     a.acc_in = comp_in;
     a.n_workers = (float)n_workers;
     const int NT = gvq_long_nt(h->k);
-    return h->dtype == GVQ_BF16 ? compress_long_nt<true>(h, a, NT, st) : compress_long_nt<false>(h, a, NT, st);
+    return h->dtype == GVQ_BF16 ? compress_long_nt<true, false>(h, a, NT, st)
+                                : compress_long_nt<false, false>(h, a, NT, st);
+}
+
+// Per-slice squared residuals of Eq. (6) into loss_slice[S]; the caller sums them per basis.
+int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, float* loss_slice, hipStream_t st)
+{
+    LongArgs a = long_args(h, grad, loss_slice, h->d_Upc, 0, h->S);
+    a.Upack2 = (const f4*)h->d_Upd;
+    a.n_workers = (float)n_workers;
+    const int NT = gvq_long_nt(h->k);
+    return h->dtype == GVQ_BF16 ? compress_long_nt<true, true>(h, a, NT, st)
+                                : compress_long_nt<false, true>(h, a, NT, st);
 }
 
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,

@@ -92,6 +92,7 @@ int64_t gvq_long_tiles(int64_t slices);       // 128-slice tiles that cover this
 int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st);
 int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
                              int64_t n_slices, const float* comp_in, float* out, hipStream_t st);
+int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, float* loss_slice, hipStream_t st);
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                                void* out, gvq_dtype_t odt, hipStream_t st);
 int gvq_large_groups(int d);
