@@ -1,4 +1,5 @@
-"""The five benchmark workloads (shapes only; no arithmetic of the method here).
+"""The five benchmark workloads and one long-slice workload (shapes only; no arithmetic of
+the method here).
 
 Each is a synthetic stand-in for the flattened convolutional gradient of a CNN of that
 size: a planted low-rank linear model per slice plus isotropic noise, which gives the
@@ -53,4 +54,7 @@ WORKLOADS = {
     "vgg16": Workload("vgg16", 138_357_544, 128, 32, 16, 32, "f32", 24, 0.05, seed=1004),
     "vgg16_bf16": Workload("vgg16_bf16", 138_357_544, 128, 16, 16, 32, "bf16", 24, 0.05,
                            block_elems=1_000_000, seed=1005),
+    # the slice size of the paper's own example (Section 3: 768 = 3 x 16 x 16 for a
+    # (3,3,16,16) layer) at 8x compression, on a gradient of the vgg16 workload's size
+    "conv768": Workload("conv768", 138_357_544, 768, 96, 8, 8, "f32", 24, 0.05, seed=1006),
 }

@@ -14,6 +14,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 NAMES = ["tiny", "resnet50", "alexnet", "vgg16", "vgg16_bf16"]
+CODEC_NAMES = NAMES + ["conv768"]   # the long-slice workload: codec only (its fit is covered at smaller sizes)
 
 
 def _sample_blocks(w):
@@ -101,14 +102,19 @@ def _rel(a, b):
     return float((a - b).norm() / b.norm())
 
 
-@pytest.mark.parametrize("name", NAMES)
+@pytest.mark.parametrize("name", CODEC_NAMES)
 def test_fullsize_codec(name):
     w = WORKLOADS[name]
     rng = np.random.default_rng(w.seed)
     blocks = _sample_blocks(w)
-    fit_np = [synth.to_numpy(g) for g in synth.fit_gradients(w, DEV, L=2)]
-    U, mu, _ = _oracle_basis_on_blocks(w, fit_np, blocks, rng)
-    del fit_np
+    if w.d > 128:
+        # the oracle's eigensolver needs minutes at this size: any orthonormal basis serves the codec
+        U = np.linalg.qr(rng.standard_normal((w.d, w.k)))[0][None]
+        mu = 0.01 * rng.standard_normal((1, w.d))
+    else:
+        fit_np = [synth.to_numpy(g) for g in synth.fit_gradients(w, DEV, L=2)]
+        U, mu, _ = _oracle_basis_on_blocks(w, fit_np, blocks, rng)
+        del fit_np
     U32, mu32 = U.astype(np.float32), mu.astype(np.float32)
     U64, mu64 = U32.astype(np.float64), mu32.astype(np.float64)
 
