@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-MFMA_F32_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 
 def main():
@@ -169,14 +169,16 @@ def main():
                      "frac": round(comp_bytes / comp_ms / 1e6 / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes_per_launch": comp_bytes, "traffic": traffic},
     }
-    # long slices with many components: 2dk flop per slice on the fp32 matrix pipe take longer at its
-    # peak than the slice's bytes take at the HBM peak -- then that pipe is the roofline
-    comp_flop = 2.0 * S * w.d * w.k
-    if w.dtype == "f32" and comp_flop / (MFMA_F32_PEAK_TFLOPS * 1e12) > comp_bytes / (HBM_PEAK_GBS * 1e9):
-        res["roofline"] = {"bound": "mfma", "kernel": "compress", "achieved": round(comp_flop / comp_ms / 1e9, 2),
-                           "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(comp_flop / comp_ms / 1e9 / MFMA_F32_PEAK_TFLOPS, 4),
-                           "algorithmic_flop_per_launch": comp_flop, "traffic": None}
+    # slices longer than 128 elements multiply on the bf16 matrix pipe (three products of bf16 terms per
+    # fp32 product): should that ever take longer at its peak than the bytes take at the HBM peak, the
+    # pipe is the roofline
+    if w.d > 128:
+        split_flop = 3 * 2.0 * S * w.d * w.k
+        if split_flop / (MFMA_BF16_PEAK_TFLOPS * 1e12) > comp_bytes / (HBM_PEAK_GBS * 1e9):
+            res["roofline"] = {"bound": "mfma", "kernel": "compress", "achieved": round(split_flop / comp_ms / 1e9, 2),
+                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": round(split_flop / comp_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                               "algorithmic_flop_per_launch": split_flop, "traffic": None}
 
     # ---- the float64 oracle on the host cores, same inputs, bounded sample --------------------
     if not args.no_cpu_baseline:

@@ -215,8 +215,14 @@ const char* gvq_strerror(int status);
  * Launch tuning (benchmarks only), process-wide; value 0 restores the default.
  *   option 0: workgroups per compute unit for the streaming kernels;
  *   option 1: consecutive 16-slice tiles a wave takes before it jumps ahead by the width
- *             of the whole grid (1 = interleave single tiles, large = one chunk per wave).
- * Returns GVQ_EINVAL for unknown options or negative values.
+ *             of the whole grid (1 = interleave single tiles, large = one chunk per wave);
+ *   option 2: matrix pipe of the codec for slices longer than 128 elements: 0 or 2 = products
+ *             of two-term bf16 splits with fp32 accumulation (the default: each product good to
+ *             about 1e-5 of its magnitude, results within 1e-5 of the exact ones relative to the
+ *             largest value), 1 = exact fp32 products (up to 2 times slower where 2dk/(4(d+k))
+ *             exceeds about 20 flop per byte).  Slices of at most 128 elements always use exact
+ *             fp32 products.
+ * Returns GVQ_EINVAL for unknown options or values out of range.
  */
 int gvq_set_option(int option, int value);
 

@@ -13,6 +13,7 @@ static thread_local char g_hip_msg[256] = "no HIP error recorded";
 static thread_local char g_msg[320];
 static int g_wg_per_cu = 0;
 static int g_run_tiles = 0;
+static int g_long_mode = 0;
 
 int gvq_hip_fail(hipError_t e, const char* what)
 {
@@ -23,6 +24,7 @@ int gvq_hip_fail(hipError_t e, const char* what)
 
 int gvq_opt_wg_per_cu() { return g_wg_per_cu; }
 int gvq_opt_run_tiles() { return g_run_tiles; }
+int gvq_opt_long_mode() { return g_long_mode; }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -49,6 +51,7 @@ int gvq_set_option(int option, int value)
 {
     if (option == 0 && value >= 0 && value <= 64) { g_wg_per_cu = value; return GVQ_OK; }
     if (option == 1 && value >= 0) { g_run_tiles = value; return GVQ_OK; }
+    if (option == 2 && value >= 0 && value <= 2) { g_long_mode = value; return GVQ_OK; }
     return GVQ_EINVAL;
 }
 
@@ -137,6 +140,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             const size_t pf = gvq_long_pack_floats(d, k);
             TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * pf));
             TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * pf));
+            TRY(hipMalloc((void**)&h->d_Upb, sizeof(unsigned short) * B * 2 * gvq_long_split_pack_halves(d, k)));
             if (n_blocks > 1) {
                 h->h_ltile = (int64_t*)malloc(sizeof(int64_t) * (B + 1));
                 if (!h->h_ltile) { rc = GVQ_ENOMEM; goto fail; }

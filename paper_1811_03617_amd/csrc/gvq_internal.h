@@ -24,7 +24,8 @@ struct gvq_basis {
     float* d_Upc = nullptr;     // [B][d][KP] U in compress-MFMA operand order (MFMA shapes only; long slices:
                                 // d rounded up to 64, KP = 16 * gvq_long_nt(k))
     float* d_Upd = nullptr;     // [B][d][KP] U in decompress-MFMA operand order
-    unsigned short* d_Upb = nullptr;  // [B][d/32][3][NT][64][8] bf16 three-term split of U (bf16 gradients)
+    unsigned short* d_Upb = nullptr;  // [B][d/32][3][NT][64][8] bf16 three-term split of U (bf16 gradients);
+                                      // long slices: the two-term copies, compress order then decompress order
     float* d_Umu = nullptr;     // [B][KP] U^T mu (bf16 gradients)
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
@@ -64,6 +65,8 @@ int gvq_hip_fail(hipError_t e, const char* what);
 int gvq_opt_wg_per_cu();
 // Tiles per run in the MFMA kernels' schedule (0 = default).
 int gvq_opt_run_tiles();
+// Long-slice codec: 1 = fp32 products, anything else = the bf16 split (default).
+int gvq_opt_long_mode();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
@@ -88,6 +91,7 @@ int gvq_moments_streams(int d);   // sample streams (partial slots) per work-gro
 // Long slices (d > GVQ_LDS_EIGEN_MAX_D): moments in 64 x 64 blocks, Jacobi out of global memory.
 bool gvq_long_shape(int d, int k);            // codec: LDS-tiled MFMA kernels for d > 128, k <= 128
 size_t gvq_long_pack_floats(int d, int k);    // floats per basis in either operand-order copy of U
+size_t gvq_long_split_pack_halves(int d, int k);   // bf16 values per basis in either two-term copy of U
 int64_t gvq_long_tiles(int64_t slices);       // 128-slice tiles that cover this many slices of one basis
 int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st);
 int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,

@@ -203,8 +203,18 @@ def _check_codec(w, out_dtype=None):
     (129 * 400 + 128, 129, 3, 2, "bf16", 129 * 100),
     (300, 512, 8, 2, "f32", 0),                      # a single partial slice
 ])
-def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems):
-    _check_codec(_wl(M, d, k, N, 2, dtype=dtype, block_elems=block_elems))
+@pytest.mark.parametrize("pipe", [1, 2], ids=["fp32-products", "bf16-split-products"])
+def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
+    assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
+    try:
+        _check_codec(_wl(M, d, k, N, 2, dtype=dtype, block_elems=block_elems))
+    finally:
+        gvq.lib().gvq_set_option(2, 0)
+
+
+def test_pipe_option_range():
+    assert gvq.lib().gvq_set_option(2, 3) == gvq.EINVAL
+    assert gvq.lib().gvq_set_option(2, 0) == gvq.OK
 
 
 def test_select_k_on_a_long_slice():

@@ -34,6 +34,18 @@ CASES = [
 
 @pytest.mark.parametrize("M,d,k,dtype,block_elems", CASES)
 def test_segment_calls_match_the_oracle_and_touch_nothing_else(M, d, k, dtype, block_elems):
+    if d <= 128:
+        _check_segments(M, d, k, dtype, block_elems)
+        return
+    for pipe in (1, 2):   # long slices: fp32 products, then products of bf16 splits
+        assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
+        try:
+            _check_segments(M, d, k, dtype, block_elems)
+        finally:
+            gvq.lib().gvq_set_option(2, 0)
+
+
+def _check_segments(M, d, k, dtype, block_elems):
     w = _wl(M, d, k, 3, dtype, block_elems)
     offs = w.block_offsets()
     U32, mu32 = _basis(w)
