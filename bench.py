@@ -34,6 +34,9 @@ def main():
                          "copy of S*k floats, the known-size kernel that HBM byte counters are scaled by")
     ap.add_argument("--fit-gradients", type=int, default=None,
                     help="override L (gradients the basis is fitted on)")
+    ap.add_argument("--skip-fit", action="store_true",
+                    help="import a seeded random orthonormal basis instead of fitting one (counter runs: the "
+                         "long-slice fit enqueues tens of thousands of small kernels)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (the N workers are simulated as N "
@@ -57,7 +60,7 @@ def main():
     basis = gvq.Basis(w.M, w.d, w.k, w.block_offsets(), w.dtype)
     S = basis.S
     workers = synth.worker_gradients(w, dev)
-    fit_grads = synth.fit_gradients(w, dev, L=L)
+    fit_grads = [] if args.skip_fit else synth.fit_gradients(w, dev, L=L)
     comps = [torch.empty(S * w.k, device=dev, dtype=torch.float32) for _ in range(w.N)]
     total = torch.empty(S * w.k, device=dev, dtype=torch.float32)
     out = torch.empty(w.M, device=dev, dtype=tdt)
@@ -67,14 +70,20 @@ def main():
         return torch.cuda.Event(enable_timing=True)
 
     # ---- basis refresh (timed on its own) -----------------------------------------------
-    basis.fit(fit_grads)
-    sweeps = basis.fit_status()
-    e0, e1 = ev(), ev()
-    e0.record()
-    basis.fit(fit_grads)
-    e1.record()
-    torch.cuda.synchronize()
-    fit_ms = e0.elapsed_time(e1)
+    if args.skip_fit:
+        rng = np.random.default_rng(w.seed)
+        U0 = np.stack([np.linalg.qr(rng.standard_normal((w.d, w.k)))[0] for _ in range(w.n_blocks)])
+        basis.import_(U0.astype(np.float32), np.zeros((w.n_blocks, w.d), np.float32))
+        sweeps, fit_ms = None, float("nan")
+    else:
+        basis.fit(fit_grads)
+        sweeps = basis.fit_status()
+        e0, e1 = ev(), ev()
+        e0.record()
+        basis.fit(fit_grads)
+        e1.record()
+        torch.cuda.synchronize()
+        fit_ms = e0.elapsed_time(e1)
     del fit_grads
 
     def step(events=None):
@@ -161,8 +170,8 @@ def main():
         "kernels_GBs": {"compress": round(comp_bytes / comp_ms / 1e6, 1),
                         "aggregate": round(agg_bytes / agg_ms / 1e6, 1),
                         "decompress": round(dec_bytes / dec_ms / 1e6, 1)},
-        "fit": {"ms": round(fit_ms, 3), "L": L, "jacobi_sweeps": sweeps,
-                "input_GBs": round(L * w.M * es / fit_ms / 1e6, 1)},
+        "fit": None if args.skip_fit else {"ms": round(fit_ms, 3), "L": L, "jacobi_sweeps": sweeps,
+                                            "input_GBs": round(L * w.M * es / fit_ms / 1e6, 1)},
         "reconstruction_loss": loss,
         "roofline": {"bound": "hbm", "kernel": "compress", "achieved": round(comp_bytes / comp_ms / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
