@@ -231,6 +231,22 @@ def test_select_k_on_a_long_slice():
     b.close()
 
 
+@pytest.mark.parametrize("first_slice_only,L", [(False, 2), (True, 6), (True, 200)])
+def test_fit_reports_non_finite_input(first_slice_only, L):
+    """NaN in a sample reaches the eigenvalues on every route (blocked moments + global-memory Jacobi,
+    sample-Gram route, first-slice moments + global-memory Jacobi) and is reported, not hidden."""
+    M, d, k = 256 * 40, 256, 8
+    gen = torch.Generator().manual_seed(4)
+    grads = [torch.randn(M, generator=gen) for _ in range(L)]
+    grads[L // 2][37] = float("nan")
+    b = gvq.Basis(M, d, k)
+    b.fit([g.to(DEV) for g in grads], first_slice_only=first_slice_only)
+    with pytest.raises(gvq.GvqError) as ei:
+        b.fit_status()
+    assert ei.value.status == gvq.ENONFINITE
+    b.close()
+
+
 def test_slice_length_limits():
     import ctypes as C
     L = gvq.lib()
