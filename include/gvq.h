@@ -216,12 +216,12 @@ const char* gvq_strerror(int status);
  *   option 0: workgroups per compute unit for the streaming kernels;
  *   option 1: consecutive 16-slice tiles a wave takes before it jumps ahead by the width
  *             of the whole grid (1 = interleave single tiles, large = one chunk per wave);
- *   option 2: matrix pipe of the codec for slices longer than 128 elements: 0 or 2 = products
- *             of two-term bf16 splits with fp32 accumulation (the default: each product good to
+ *   option 2: matrix pipe of the LDS-tiled codec kernels (slices longer than 128 elements, and
+ *             shorter shapes other than d in {16,32,64,128} with k <= 32): 0 = exact fp32
+ *             products where they keep up with memory (2dk/(4(d+k)) < 10 flop per byte),
+ *             else products of two-term bf16 splits with fp32 accumulation (each product good to
  *             about 1e-5 of its magnitude, results within 1e-5 of the exact ones relative to the
- *             largest value), 1 = exact fp32 products (up to 2 times slower where 2dk/(4(d+k))
- *             exceeds about 20 flop per byte).  Slices of at most 128 elements always use exact
- *             fp32 products.
+ *             largest value, up to 2 times faster); 1 = always exact products; 2 = always the split.
  * Returns GVQ_EINVAL for unknown options or values out of range.
  */
 int gvq_set_option(int option, int value);

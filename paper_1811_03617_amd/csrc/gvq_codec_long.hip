@@ -1,6 +1,8 @@
 // Codec kernels for long slices, 128 < d <= GVQ_MAX_D and k <= 128 (GradiVeQ Eqs. 2 and 4 with
-// the slice sizes of Section 3, e.g. d = 768).  U (d x k floats, up to 512 KB) no longer fits a
-// wave's registers, so these are LDS-tiled contractions on v_mfma_f32_16x16x4_f32:
+// the slice sizes of Section 3, e.g. d = 768), also used for every shorter shape that the
+// register-resident kernels do not take (d not in {16,32,64,128}, or k > 32).  U (d x k floats, up
+// to 512 KB) does not fit a wave's registers, so these are LDS-tiled contractions on the matrix
+// pipes (first the exact fp32 products on v_mfma_f32_16x16x4_f32, further down the bf16 split):
 //   a work-group of 4 waves owns LW_SLICES = 128 consecutive slices of one basis, 32 per wave
 //   (two 16-slice MFMA column tiles);  U is streamed through LDS in chunks of LC = 64 elements,
 //   double-buffered, one s_barrier per chunk, shared by the 4 waves;  the gradient side goes
@@ -11,6 +13,8 @@
 
 #define LW_SLICES 128
 #define LC 64
+// first element (inside a chunk) of word i of lane group kk in the compress kernels
+#define LWORD(i, kk) (32 * ((i) >> 1) + 8 * (kk) + 4 * ((i) & 1))
 
 struct LongArgs {
     const void* in;
@@ -46,7 +50,7 @@ __device__ __forceinline__ void long_tile(const LongArgs& a, int64_t tile, int& 
 
 // 4 consecutive gradient elements starting at element e of slice s, zero where the slice or the
 // gradient ends (the zero padding of the last slice).  FAST: the caller guarantees that d is a
-// multiple of 64 and that every slice of the tile lies wholly inside the gradient; the load is
+// multiple of 4 and that every slice of the tile lies wholly inside the gradient; the load is
 // then unconditional from `row` (the start of the lane's slice, or of the tile's last slice for
 // lanes past its end, whose results are dropped), which keeps the number of loads in flight
 // known to the compiler, so that it waits for the words it needs and not for the requests
@@ -56,15 +60,19 @@ __device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s,
 {
     f4 v = {0.f, 0.f, 0.f, 0.f};
     if (FAST) {
+        const bool inside = e < a.d;            // past the slice (last chunk, d not a multiple of 64):
+        const int ec = inside ? e : a.d - 4;    // read its last word instead and drop the value
         if (BF16) {
-            const u2 w = *(const u2*)((const unsigned short*)row + e);
+            const u2 w = *(const u2*)((const unsigned short*)row + ec);
             v[0] = __uint_as_float(w.x << 16);
             v[1] = __uint_as_float(w.x & 0xffff0000u);
             v[2] = __uint_as_float(w.y << 16);
             v[3] = __uint_as_float(w.y & 0xffff0000u);
         } else {
-            v = *(const f4*)((const float*)row + e);
+            v = *(const f4*)((const float*)row + ec);
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = inside ? v[r] : 0.f;
         return v;
     }
     if (!row_ok || e >= a.d) return v;
@@ -77,10 +85,12 @@ __device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s,
 }
 
 // --------------------------------------------------------------------------------------
-// compress: D[comp][slice] += U[elem][comp] x[slice][elem].  For chunk c, load i (0..3) and
-// step j (0..3), lane (m, kk) of the A operand holds U[64c + 16i + 4kk + j][16nt + m] and lane
-// (n, kk) of the B operand x[slice n][64c + 16i + 4kk + j] - mu/N: one 128-bit word of x feeds
-// four steps.  Result register r of lane (n, kk) is comp 16nt + 4kk + r of slice n.
+// compress: D[comp][slice] += U[elem][comp] x[slice][elem].  For chunk c, word i (0..3) and
+// step j (0..3), lane (m, kk) of the A operand holds U[64c + w(i, kk) + j][16nt + m] and lane
+// (n, kk) of the B operand x[slice n][64c + w(i, kk) + j] - mu/N with w(i, kk) = 32(i/2) + 8kk +
+// 4(i%2): one 128-bit word of x feeds four steps, and a lane's two words of a pair are
+// adjacent, so that the four lanes of a slice read 128 contiguous bytes.  Result register r of
+// lane (n, kk) is comp 16nt + 4kk + r of slice n.
 // Upack[b][c][i][nt][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
 // --------------------------------------------------------------------------------------
 template <int NT, bool BF16, bool FAST, bool LOSS>
@@ -115,21 +125,21 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], 16 * i + 4 * kk);
+        for (int i = 0; i < 4; ++i) xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], LWORD(i, kk));
 
     for (int c = 0; c < a.nchunk; ++c) {
         const int cn = c < last ? c + 1 : last;
 #pragma unroll
         for (int q = 0; q < NT; ++q) ur[q] = Ub[(size_t)cn * CH4 + tid + 256 * q];
         const f4* Uc = Us + (c & 1) * CH4;
-        const float* mc = mus + c * LC + 4 * kk;
+        const float* mc = mus + c * LC;
         // MFMA steps (i, g): the LDS operands of step st + 1 are requested before the MFMAs of
         // step st are issued; inside a step the accumulators are innermost, 2 G independent
         // chains between two uses of one
         f4 uw[2][G], mw[2];
 #pragma unroll
         for (int q = 0; q < G; ++q) uw[0][q] = Uc[q * 64 + lane];
-        mw[0] = *(const f4*)mc;
+        mw[0] = *(const f4*)(mc + LWORD(0, kk));
         __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) {
@@ -138,7 +148,7 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
                 const int i1 = (st + 1) / NG, g1 = (st + 1) % NG;
 #pragma unroll
                 for (int q = 0; q < G; ++q) uw[(st + 1) & 1][q] = Uc[(i1 * NT + g1 * G + q) * 64 + lane];
-                if (g1 == 0) mw[i1 & 1] = *(const f4*)(mc + 16 * i1);
+                if (g1 == 0) mw[i1 & 1] = *(const f4*)(mc + LWORD(i1, kk));
             }
             const f4 x0 = xr[0][i] - mw[i & 1], x1 = xr[1][i] - mw[i & 1];
 #pragma unroll
@@ -152,7 +162,7 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
             if (g == NG - 1) {   // word i is used up
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
-                    xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 16 * i + 4 * kk);
+                    xr[t][i] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + LWORD(i, kk));
             }
         }
         __builtin_amdgcn_s_setprio(0);
@@ -218,7 +228,7 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         // only elements that exist count (not the zero padding of the last slice)
-                        const bool real = FAST ? true : (e0 + r < a.d && s[t] * a.d + e0 + r < a.M);
+                        const bool real = FAST ? e0 < a.d : (e0 + r < a.d && s[t] * a.d + e0 + r < a.M);
                         if (real) sq[t] = fmaf(res[r], res[r], sq[t]);
                     }
                     xr[t][et] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 16 * et + 4 * kk);
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
         __syncthreads();
         const f4* Ub2 = LOSS ? a.Upack2 + (size_t)b * a.nchunk * CH4 : nullptr;
-        if ((a.d & 63) == 0 && end * a.d <= a.M)
+        if ((a.d & 3) == 0 && end * a.d <= a.M)
             compress_long_tile<NT, BF16, true, LOSS>(a, Us, mus, Ub, Ub2, first, end, lo, hi);
         else
             compress_long_tile<NT, BF16, false, LOSS>(a, Us, mus, Ub, Ub2, first, end, lo, hi);
@@ -568,7 +578,7 @@ __global__ __launch_bounds__(256, 2) void compress_split_kernel(LongArgs a)
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
         __syncthreads();
-        if ((a.d & 63) == 0 && end * a.d <= a.M)
+        if ((a.d & 3) == 0 && end * a.d <= a.M)
             compress_split_tile<NT, BF16, true>(a, Us, mus, Ub, first, end, lo, hi);
         else
             compress_split_tile<NT, BF16, false>(a, Us, mus, Ub, first, end, lo, hi);
@@ -733,7 +743,7 @@ __global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, 
         const size_t hi = i >> 8;
         const int inner = (int)(hi % NT), outer = (int)((hi / NT) & 3), c = (int)(hi / (4 * NT));
         {   // compress order: outer = i (load), inner = nt
-            const int e = c * LC + 16 * outer + 4 * kk + j, comp = 16 * inner + m;
+            const int e = c * LC + LWORD(outer, kk) + j, comp = 16 * inner + m;
             Upc[(size_t)b * per + i] = (e < d && comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
         }
         {   // decompress order: outer = et, inner = w
@@ -746,7 +756,8 @@ __global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, 
 // ======================================================================================
 // host side
 // ======================================================================================
-bool gvq_long_shape(int d, int k) { return d > 128 && k <= 128; }
+// Every shape the register-resident kernels for d in {16,32,64,128}, k <= 32 do not take.
+bool gvq_long_shape(int d, int k) { return k <= 128 && !gvq_mfma_shape(d, k); }
 int gvq_long_nt(int k) { return k <= 16 ? 1 : k <= 32 ? 2 : k <= 64 ? 4 : k <= 96 ? 6 : 8; }
 int gvq_long_chunks(int d) { return (d + LC - 1) / LC; }
 size_t gvq_long_pack_floats(int d, int k) { return (size_t)gvq_long_chunks(d) * LC * 16 * gvq_long_nt(k); }
@@ -756,13 +767,16 @@ static int split_nt(int k) { const int nt = gvq_long_nt(k); return nt < 2 ? 2 : 
 // bf16 values per basis in either split copy of U
 size_t gvq_long_split_pack_halves(int d, int k) { return (size_t)gvq_long_chunks(d) * 4 * split_nt(k) * 64 * 8; }
 
-// The split kernels are the default: measured at least as fast as the fp32-product kernels on every
-// shape (equal where memory binds either way, 1.7 to 2.1 times faster where the fp32 pipe would
-// bind) and within 1e-5 of them relative to the largest value.  Option 2 = 1 selects the fp32 products.
+// Which matrix pipe: exact fp32 products while they keep up with memory (2dk / (4(d + k)) below 10
+// flop per byte; at 14, d = 256 and k = 32, the fp32 decompress already falls a quarter behind the
+// split one), the bf16 split above that.  Option 2 overrides: 1 = always fp32 products, 2 = always
+// the split.
 bool gvq_long_split(const gvq_basis* h)
 {
-    (void)h;
-    return gvq_opt_long_mode() != 1;
+    const int mode = gvq_opt_long_mode();
+    if (mode == 1) return false;
+    if (mode == 2) return true;
+    return 2.0 * h->d * h->k / (4.0 * (h->d + h->k)) >= 10.0;
 }
 
 int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st)

@@ -65,7 +65,7 @@ int gvq_hip_fail(hipError_t e, const char* what);
 int gvq_opt_wg_per_cu();
 // Tiles per run in the MFMA kernels' schedule (0 = default).
 int gvq_opt_run_tiles();
-// Long-slice codec: 1 = fp32 products, anything else = the bf16 split (default).
+// LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split.
 int gvq_opt_long_mode();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
@@ -89,7 +89,8 @@ bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
 // Long slices (d > GVQ_LDS_EIGEN_MAX_D): moments in 64 x 64 blocks, Jacobi out of global memory.
-bool gvq_long_shape(int d, int k);            // codec: LDS-tiled MFMA kernels for d > 128, k <= 128
+bool gvq_long_shape(int d, int k);            // codec: the LDS-tiled MFMA kernels take this shape (d > 128, or any
+                                              // shape with k <= 128 that the register-resident kernels do not)
 size_t gvq_long_pack_floats(int d, int k);    // floats per basis in either operand-order copy of U
 size_t gvq_long_split_pack_halves(int d, int k);   // bf16 values per basis in either two-term copy of U
 int64_t gvq_long_tiles(int64_t slices);       // 128-slice tiles that cover this many slices of one basis
