@@ -107,7 +107,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         h->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
         size_t width = (size_t)d * d + d;
         size_t part_doubles = 0;   // per basis, when not P * width
-        if (d > GVQ_LDS_EIGEN_MAX_D) {
+        if (!gvq_moments_mfma_shape(d)) {
             // one wave per (64 x 64 block, sample chunk): enough chunks for about two waves per
             // SIMD over all bases, never less than 64 sample slices per chunk
             const int64_t ng = gvq_large_groups(d), npairs = ng * (ng + 1) / 2;
@@ -116,7 +116,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             if (chunks < 1) chunks = 1;
             h->P = (int)chunks;
             part_doubles = gvq_large_partial_doubles(d, h->P);
-        } else if (gvq_moments_mfma_shape(d)) {
+        } else {
             // two work-groups of 4 waves per compute unit, spread over the bases; never less
             // than 64 sample slices per stream
             const int streams = gvq_moments_streams(d);
@@ -126,11 +126,6 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             h->mom_wgs = (int)wgs;
             h->P = (int)wgs * streams;
             width = (size_t)gvq_moments_packed_width(d);
-        } else {
-            int64_t P = (4LL * h->num_cu + n_blocks - 1) / n_blocks;
-            if (P > (longest + 63) / 64) P = (longest + 63) / 64;
-            if (P < 1) P = 1;
-            h->P = (int)P;
         }
         const size_t B = (size_t)n_blocks, W = (size_t)d * d + d, n = (size_t)(d + (d & 1));
         TRY(hipMalloc((void**)&h->d_offs, sizeof(int64_t) * (B + 1)));
@@ -162,10 +157,12 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
         TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
-        if (part_doubles) {
-            TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * part_doubles));
+        if (d > GVQ_LDS_EIGEN_MAX_D) {
             TRY(hipMalloc((void**)&h->d_jac, sizeof(double) * B * 2 * n * n));
             TRY(hipMalloc((void**)&h->d_jstate, sizeof(int) * B * 4));
+        }
+        if (part_doubles) {
+            TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * part_doubles));
         } else {
             TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * (size_t)h->P * width));
             TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));

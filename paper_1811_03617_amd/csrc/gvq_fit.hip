@@ -6,112 +6,10 @@
 //                one workgroup per basis; sort, keep k columns, fix signs.
 #include "gvq_internal.h"
 
-#define MOM_THREADS 256
-#define MOM_TILE 32  // slices staged in LDS per step
-
-struct MomArgs {
-    gvq_ptrs grads;
-    int L;
-    const int64_t* offs;
-    int64_t M;
-    int d, P;
-    double* part;  // [B][P][d*d+d]
-};
-
 __device__ __forceinline__ float load_elem(const void* g, bool bf16, int64_t idx)
 {
     if (bf16) return __uint_as_float((unsigned int)((const unsigned short*)g)[idx] << 16);
     return ((const float*)g)[idx];
-}
-
-// Thread (ti, tj) of a 16x16 thread grid owns the TB x TB block of sum x x^T with rows
-// ti*TB.. and columns tj*TB..; d is padded with zeros to 16*TB.
-template <int TB, bool BF16>
-__global__ __launch_bounds__(MOM_THREADS) void moments_kernel(MomArgs a)
-{
-    constexpr int DP = 16 * TB;
-    __shared__ float xs[MOM_TILE][DP];
-    const int tid = threadIdx.x, ti = tid >> 4, tj = tid & 15;
-    const int b = blockIdx.y, p = blockIdx.x;
-    const int d = a.d;
-
-    const int64_t full = a.M / d;  // full slices in a gradient
-    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
-    if (hi < lo) hi = lo;
-    const int64_t cnt = hi - lo;
-    const int64_t j0 = lo + cnt * p / a.P, j1 = lo + cnt * (p + 1) / a.P;
-
-    double acc[TB][TB];
-    double sacc[TB];
-#pragma unroll
-    for (int i = 0; i < TB; ++i) {
-        sacc[i] = 0.0;
-#pragma unroll
-        for (int j = 0; j < TB; ++j) acc[i][j] = 0.0;
-    }
-    for (int i = tid; i < MOM_TILE * DP; i += MOM_THREADS) (&xs[0][0])[i] = 0.f;
-
-    for (int l = 0; l < a.L; ++l) {
-        const void* g = a.grads.p[l];
-        for (int64_t c0 = j0; c0 < j1; c0 += MOM_TILE) {
-            const int ns = (int)(j1 - c0 < MOM_TILE ? j1 - c0 : MOM_TILE);
-            __syncthreads();
-            for (int i = tid; i < ns * d; i += MOM_THREADS) {
-                int s = i / d, e = i - s * d;
-                xs[s][e] = load_elem(g, BF16, c0 * d + i);
-            }
-            __syncthreads();
-            for (int s = 0; s < ns; ++s) {
-                double xr[TB], xc[TB];
-#pragma unroll
-                for (int i = 0; i < TB; ++i) {
-                    xr[i] = (double)xs[s][ti * TB + i];
-                    xc[i] = (double)xs[s][tj * TB + i];
-                }
-#pragma unroll
-                for (int i = 0; i < TB; ++i)
-#pragma unroll
-                    for (int j = 0; j < TB; ++j) acc[i][j] = fma(xr[i], xc[j], acc[i][j]);
-                if (ti == 0) {
-#pragma unroll
-                    for (int j = 0; j < TB; ++j) sacc[j] += xc[j];
-                }
-            }
-        }
-    }
-    double* out = a.part + ((size_t)b * a.P + p) * (size_t)(d * d + d);
-#pragma unroll
-    for (int i = 0; i < TB; ++i)
-#pragma unroll
-        for (int j = 0; j < TB; ++j) {
-            int r = ti * TB + i, c = tj * TB + j;
-            if (r < d && c < d) out[r * d + c] += acc[i][j];
-        }
-    if (ti == 0) {
-#pragma unroll
-        for (int j = 0; j < TB; ++j) {
-            int c = tj * TB + j;
-            if (c < d) out[d * d + c] += sacc[j];
-        }
-    }
-}
-
-__global__ void fill_zero_kernel(double* p, int64_t n)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-        p[i] = 0.0;
-}
-
-// mom[b][e] = part[b][0][e] + part[b][1][e] + ... in that order.
-__global__ void reduce_partials_kernel(const double* part, double* mom, int P, int W)
-{
-    const int b = blockIdx.y;
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= W) return;
-    const double* src = part + (size_t)b * P * W + e;
-    double acc = 0.0;
-    for (int p = 0; p < P; ++p) acc += src[(size_t)p * W];
-    mom[(size_t)b * W + e] = acc;
 }
 
 // --------------------------------------------------------------------------------------
@@ -753,16 +651,6 @@ int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st)
 }
 
 // ======================================================================================
-template <int TB>
-static void launch_moments(const gvq_basis* h, const MomArgs& a, hipStream_t st)
-{
-    dim3 grid(h->P, h->B);
-    if (h->dtype == GVQ_BF16)
-        hipLaunchKernelGGL((moments_kernel<TB, true>), grid, dim3(MOM_THREADS), 0, st, a);
-    else
-        hipLaunchKernelGGL((moments_kernel<TB, false>), grid, dim3(MOM_THREADS), 0, st, a);
-}
-
 size_t gvq_eigen_lds_bytes(int d)
 {
     const int n = d + (d & 1), half = n / 2;
@@ -796,10 +684,10 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
                                h->dtype == GVQ_BF16 ? 1 : 0, l0 > 0 ? 1 : 0, h->d_mom);
             GVQ_HIP(hipGetLastError());
         }
-    } else if (d > GVQ_LDS_EIGEN_MAX_D) {
+    } else if (!gvq_moments_mfma_shape(d)) {
         const int rc = gvq_launch_moments_large(h, grads, L, st);
         if (rc != GVQ_OK) return rc;
-    } else if (gvq_moments_mfma_shape(d)) {
+    } else {
         const int WP = mom_packed_width(d);
         for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
             MomMfmaArgs a;
@@ -824,24 +712,6 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         GVQ_HIP(hipGetLastError());
         hipLaunchKernelGGL(unpack_moments_kernel, dim3((WP + 255) / 256, h->B), dim3(256), 0, st,
                            h->d_part, h->d_mom, d);
-        GVQ_HIP(hipGetLastError());
-    } else {
-        const int64_t npart = (int64_t)h->B * h->P * W;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, st, h->d_part, npart);
-        GVQ_HIP(hipGetLastError());
-        for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
-            MomArgs a;
-            a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
-            for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
-            a.offs = h->d_offs; a.M = h->M; a.d = d; a.P = h->P; a.part = h->d_part;
-            if (d <= 16) launch_moments<1>(h, a, st);
-            else if (d <= 32) launch_moments<2>(h, a, st);
-            else if (d <= 64) launch_moments<4>(h, a, st);
-            else launch_moments<8>(h, a, st);
-            GVQ_HIP(hipGetLastError());
-        }
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((W + 255) / 256, h->B), dim3(256), 0, st,
-                           h->d_part, h->d_mom, h->P, W);
         GVQ_HIP(hipGetLastError());
     }
 

@@ -2,7 +2,8 @@
 // slice is a multiple of a layer's filters x depth, e.g. 768 for a (3,3,16,16) layer).  The
 // d x d matrix no longer fits one work-group's LDS, so both stages work out of global memory:
 //   moments: sum x x^T in 64 x 64 blocks on the fp64 matrix pipe, one wave per (block, sample
-//            chunk), fixed-order sum of the chunks afterwards;
+//            chunk), fixed-order sum of the chunks afterwards (any d: also used for the short
+//            slice lengths other than 16, 32, 64 and 128);
 //   eigen:   the same parallel-order two-sided Jacobi as for short slices, one kernel launch per
 //            round of disjoint rotations (the launch boundary is the grid-wide barrier), the
 //            matrix ping-ponging between two buffers so that a round reads only old values.

@@ -30,7 +30,8 @@ struct gvq_basis {
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
     double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
-    double* d_part = nullptr;   // [B][P][width] moment partials (width: d*d+d, or the packed width of the MFMA path)
+    double* d_part = nullptr;   // moment partials: [B][P][packed width] for d in {16,32,64,128}, else
+                                // [B][block pairs][P][64*64+64] (64 x 64 blocks, P sample chunks)
     double* d_part2 = nullptr;  // [B][ceil(P/32)][width] second level of the partial sum (MFMA path)
     int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
@@ -88,7 +89,8 @@ bool gvq_bf16_pipe_shape(const gvq_basis* h);
 bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
-// Long slices (d > GVQ_LDS_EIGEN_MAX_D): moments in 64 x 64 blocks, Jacobi out of global memory.
+// Moments in 64 x 64 blocks (every d other than 16, 32, 64, 128); Jacobi out of global memory
+// (d > GVQ_LDS_EIGEN_MAX_D).
 bool gvq_long_shape(int d, int k);            // codec: the LDS-tiled MFMA kernels take this shape (d > 128, or any
                                               // shape with k <= 128 that the register-resident kernels do not)
 size_t gvq_long_pack_floats(int d, int k);    // floats per basis in either operand-order copy of U
