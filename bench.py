@@ -127,6 +127,18 @@ def main():
     value = grad_bytes / ms_per_step / 1e6                # GB/s of gradient through the path
     eff = path_bytes / ms_per_step / 1e6
 
+    # per-step device times (first event of a step to its last) and a plain copy through the same
+    # library (gvq_aggregate of ONE vector), the practical ceiling of this memory system for a 1:1 stream
+    step_ms = sorted(m[0].elapsed_time(m[3]) for m in marks)
+    c0, c1 = ev(), ev()
+    basis.aggregate(comps[:1], total)
+    c0.record()
+    for _ in range(10):
+        basis.aggregate(comps[:1], total)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * S * 4 * w.k * 10 / c0.elapsed_time(c1) / 1e6
+
     if args.calibration_copy:
         for _ in range(3):
             basis.aggregate(comps[:1], total)
@@ -165,6 +177,8 @@ def main():
         "hbm_effective_GBs": round(eff, 1),
         "pct_of_hbm_peak": round(100.0 * eff / HBM_PEAK_GBS, 2),
         "path_algorithmic_bytes": path_bytes,
+        "ms_per_step_min": round(step_ms[0], 4), "ms_per_step_median": round(step_ms[len(step_ms) // 2], 4),
+        "copy_kernel_GBs": round(copy_gbs, 1),
         "kernels_ms": {"compress_per_launch": round(comp_ms, 4), "aggregate": round(agg_ms, 4),
                        "decompress": round(dec_ms, 4)},
         "kernels_GBs": {"compress": round(comp_bytes / comp_ms / 1e6, 1),
