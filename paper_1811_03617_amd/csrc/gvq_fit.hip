@@ -596,7 +596,10 @@ __global__ __launch_bounds__(1024) void gram_eigen_kernel(GramArgs a)
 // The small-matrix route is taken when it applies and its scratch fits the eigenvector work space.
 bool gvq_gram_shape(int d, int k, int L)
 {
-    return L >= 2 && L <= GVQ_GRAM_MAX_L && 2 * L <= d && k <= GVQ_GRAM_MAX_K && 4 * (int64_t)k <= 3 * (int64_t)d;
+    // scratch: (L rounded up to even)^2 + k d doubles inside the d x d eigenvector work space
+    const int64_t m = L + (L & 1);
+    return L >= 2 && L <= GVQ_GRAM_MAX_L && 2 * L <= d && k <= GVQ_GRAM_MAX_K &&
+           m * m + (int64_t)k * d <= (int64_t)d * d;
 }
 
 // Section 3, "compressor reuse": moments of the first slice of every basis only -- L samples of d

@@ -92,6 +92,9 @@ def test_fit_parity_first_slice_of_a_768_element_slice():
     (130 * 9 + 1, 130, 7, 65, "f32", 0),               # as many samples as the small-matrix route takes
     (130 * 9 + 1, 130, 7, 66, "f32", 0),               # one more: the general solver
     (192 * 8, 192, 150, 12, "f32", 0),                 # too many columns for it: the general solver
+    (130 * 9 + 1, 130, 96, 65, "f32", 0),              # its scratch just fits the eigenvector work space
+    (130 * 9 + 1, 130, 97, 65, "f32", 0),              # ... and just does not: the general solver
+    (256 * 140, 256, 16, 128, "f32", 0),               # the largest sample matrix it takes
 ])
 def test_fit_parity_first_slice_few_samples(M, d, k, L, dtype, block_elems):
     _check_fit(_wl(M, d, k, 2, L, dtype=dtype, rank=5, sigma=0.2, block_elems=block_elems), first_slice_only=True)
