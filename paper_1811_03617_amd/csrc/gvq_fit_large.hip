@@ -289,14 +289,22 @@ __global__ __launch_bounds__(1024) void jacobi_check_kernel(JacArgs a, int sweep
     }
 }
 
+// Index pair i of the round-robin schedule in round `round` (n even): pair 0 is (round, n-1),
+// pair i is ((round + i) mod (n-1), (round - i) mod (n-1)); returned with p < q.
+__device__ __forceinline__ void jacobi_pair(int n, int round, int i, int& p, int& q)
+{
+    if (i == 0) { p = round; q = n - 1; }
+    else { p = (round + i) % (n - 1); q = (round - i + (n - 1)) % (n - 1); }
+    if (p > q) { const int u = p; p = q; q = u; }
+}
+
 // One round: the n/2 disjoint rotations (p_i, q_i) of the round-robin schedule, applied as
 // dst[{p_i,q_i}][{p_j,q_j}] = R_i^T src[..][..] R_j, one thread per 2 x 2 block, and V <- V J for
 // the rows 2i, 2i+1 and column pair j.  R = [[c, s], [-s, c]], theta = (a_qq - a_pp) / (2 a_pq),
 // t = sign(theta) / (|theta| + sqrt(theta^2 + 1)), c = 1/sqrt(1 + t^2), s = t c.  A work-group
-// covers 16 x 16 blocks and first works out its 16 + 16 rotations from the old matrix.
+// covers 16 x 16 blocks.
 __global__ __launch_bounds__(256) void jacobi_round_kernel(JacArgs a, int round, int src)
 {
-    __shared__ int sp[2][16], sq[2][16];
     __shared__ double sc[2][16], ss[2][16];
     const int b = blockIdx.z;
     if (a.state[4 * b]) return;
@@ -304,36 +312,43 @@ __global__ __launch_bounds__(256) void jacobi_round_kernel(JacArgs a, int round,
     const double* A = a.jac + ((size_t)b * 2 + src) * n * n;
     double* Bm = a.jac + ((size_t)b * 2 + (src ^ 1)) * n * n;
     double* V = a.V + (size_t)b * n * n;
+    // The pair indices are arithmetic, so a thread asks for its 2 x 2 block and its eigenvector
+    // entries right away; the 16 + 16 rotations of the work-group are worked out meanwhile by its
+    // first 32 threads (from the old matrix) and handed over through LDS: one memory round trip.
+    const int ti = tid >> 4, tj = tid & 15;
+    const int i = blockIdx.y * 16 + ti, j = blockIdx.x * 16 + tj;
+    const bool active = i < half && j < half;
+    int p = 0, q = 0, r = 0, t = 0;
+    double apr = 0.0, apt = 0.0, aqr = 0.0, aqt = 0.0, v0r = 0.0, v0t = 0.0, v1r = 0.0, v1t = 0.0;
+    const int r0 = 2 * i, r1 = 2 * i + 1;
+    if (active) {
+        jacobi_pair(n, round, i, p, q);
+        jacobi_pair(n, round, j, r, t);
+        apr = A[(size_t)p * n + r]; apt = A[(size_t)p * n + t];
+        aqr = A[(size_t)q * n + r]; aqt = A[(size_t)q * n + t];
+        v0r = V[(size_t)r0 * n + r]; v0t = V[(size_t)r0 * n + t];
+        v1r = V[(size_t)r1 * n + r]; v1t = V[(size_t)r1 * n + t];
+    }
     if (tid < 32) {
-        const int side = tid >> 4, t = tid & 15;
-        const int i = (side ? blockIdx.x : blockIdx.y) * 16 + t;
-        int p = 0, q = 0;
+        const int side = tid >> 4, u = tid & 15;
+        const int pi = (side ? blockIdx.x : blockIdx.y) * 16 + u;
         double c = 1.0, s = 0.0;
-        if (i < half) {
-            if (i == 0) { p = round; q = n - 1; }
-            else { p = (round + i) % (n - 1); q = (round - i + (n - 1)) % (n - 1); }
-            if (p > q) { const int u = p; p = q; q = u; }
-            const double apq = A[(size_t)p * n + q];
+        if (pi < half) {
+            int pp, qq;
+            jacobi_pair(n, round, pi, pp, qq);
+            const double apq = A[(size_t)pp * n + qq];
             if (apq != 0.0) {
-                const double theta = (A[(size_t)q * n + q] - A[(size_t)p * n + p]) / (2.0 * apq);
+                const double theta = (A[(size_t)qq * n + qq] - A[(size_t)pp * n + pp]) / (2.0 * apq);
                 const double tt = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
                 c = 1.0 / sqrt(1.0 + tt * tt);
                 s = tt * c;
             }
         }
-        sp[side][t] = p; sq[side][t] = q; sc[side][t] = c; ss[side][t] = s;
+        sc[side][u] = c; ss[side][u] = s;
     }
     __syncthreads();
-    const int ti = tid >> 4, tj = tid & 15;
-    const int i = blockIdx.y * 16 + ti, j = blockIdx.x * 16 + tj;
-    if (i >= half || j >= half) return;
-    const int p = sp[0][ti], q = sq[0][ti], r = sp[1][tj], t = sq[1][tj];
+    if (!active) return;
     const double ci = sc[0][ti], si = ss[0][ti], cj = sc[1][tj], sj = ss[1][tj];
-    const int r0 = 2 * i, r1 = 2 * i + 1;
-    const double v0r = V[(size_t)r0 * n + r], v0t = V[(size_t)r0 * n + t];
-    const double v1r = V[(size_t)r1 * n + r], v1t = V[(size_t)r1 * n + t];
-    const double apr = A[(size_t)p * n + r], apt = A[(size_t)p * n + t];
-    const double aqr = A[(size_t)q * n + r], aqt = A[(size_t)q * n + t];
     // rows: R_i^T * block
     const double xpr = ci * apr - si * aqr, xpt = ci * apt - si * aqt;
     const double xqr = si * apr + ci * aqr, xqt = si * apt + ci * aqt;
