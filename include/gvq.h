@@ -21,7 +21,10 @@
  *     buffers must stay valid until that work has finished;
  *   - the library owns the handle and the scratch memory inside it (allocated by
  *     gvq_basis_create, released by gvq_basis_destroy) and nothing else;
- *   - calls on one handle must not overlap in time on different streams.
+ *   - calls on one handle must not overlap in time on different streams;
+ *   - the first launch of a kernel in a process asks the runtime once for its occupancy and,
+ *     for some kernels, raises its LDS limit; these queries are not stream work, so call an
+ *     entry point once on the shapes in use before capturing it into a HIP graph.
  *
  * Layouts
  *   gradient    : M elements, fp32 or bf16 (bit pattern in 16 bits), slice j = elements
