@@ -1,5 +1,7 @@
 // Codec kernels for gfx950: compress (Eq. 2), aggregate (Eq. 3), decompress (Eq. 4) of
-// GradiVeQ, Section 2.  All three stream the gradient once; U and mu live in registers.
+// GradiVeQ, Section 2, for the shapes whose basis fits a wave's registers (d in {16,32,64,128},
+// k <= 32); every other shape with k <= 128 goes to the LDS-tiled kernels of gvq_codec_long.hip,
+// k > 128 to the one-thread-per-output kernels here.  All stream the gradient once.
 //
 // The two projections are tall-skinny contractions (inner dimension d <= 128 or k <= 32).
 // At d = 128, k = 32 they need ~13 flop per HBM byte, more than the fp32 vector units
@@ -437,7 +439,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
     }
 }
 
-// compress, any d <= 128 and k <= d: one thread per output number.  Correct, not fast.
+// compress, any d and k <= d (used for k > 128 only): one thread per output number.  Correct, not fast.
 template <bool BF16>
 __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
 {
@@ -644,7 +646,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
     (void)TILE_ELEMS;
 }
 
-// decompress, any d, k: one thread per output element.
+// decompress, any d, k (used for k > 128 only): one thread per output element.
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void decompress_generic_kernel(CodecArgs a)
 {
@@ -1014,7 +1016,8 @@ int gvq_launch_aggregate(const gvq_basis* h, const float* const* comps, int N, f
 // ======================================================================================
 // local compression loss (Section 3, Eq. 6)
 // ======================================================================================
-// Any d, k: one wave per slice.  Lanes first share the k projections, then the d residuals.
+// Any d, k (used for k > 128 only): one wave per slice.  Lanes first share the k projections, then
+// the d residuals.
 template <bool BF16>
 __global__ __launch_bounds__(256) void loss_generic_kernel(CodecArgs a)
 {
