@@ -18,20 +18,36 @@ FLAGS = [
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
+    """Compile every source to an object file (in parallel), then link the shared library."""
+    import concurrent.futures
+    import shutil
+    import tempfile
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-shared", "-o", LIB + ".tmp", *srcs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    # the host pass says it does not know the packed-fp32 target feature: harmless
-    log = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + log)
-    if verbose and log.strip():
-        print(log, flush=True)
-    os.replace(LIB + ".tmp", LIB)
+    common = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    tmp = tempfile.mkdtemp(prefix="gvq_build_")
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        # the host pass says it does not know the packed-fp32 target feature: harmless
+        log = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + log)
+        if verbose and log.strip():
+            print(log, flush=True)
+
+    try:
+        objs = [os.path.join(tmp, s + ".o") for s in SOURCES]
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+            jobs = [pool.submit(run, [*common, "-c", "-o", o, os.path.join(CSRC, s)]) for s, o in zip(SOURCES, objs)]
+            for j in jobs:
+                j.result()
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs])
+        os.replace(LIB + ".tmp", LIB)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB
 
 
