@@ -829,8 +829,16 @@ static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_
     }
     int per_cu = gvq_opt_wg_per_cu();
     if (per_cu <= 0) {
-        GVQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)KERN, 256, lds));
-        if (per_cu < 1) per_cu = 1;
+        // asked once per kernel and LDS size (the size changes with the slice length only)
+        static size_t known_lds = 0;
+        static int known_per_cu = 0;
+        if (known_per_cu == 0 || known_lds != lds) {
+            int occ = 0;
+            GVQ_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void*)KERN, 256, lds));
+            known_per_cu = occ < 1 ? 1 : occ;
+            known_lds = lds;
+        }
+        per_cu = known_per_cu;
     }
     const int64_t tiles = a.t1 - a.t0, cap = (int64_t)h->num_cu * per_cu;
     const int grid = (int)(tiles < cap ? tiles : cap);
