@@ -108,10 +108,11 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         size_t width = (size_t)d * d + d;
         size_t part_doubles = 0;   // per basis, when not P * width
         if (!gvq_moments_mfma_shape(d)) {
-            // one wave per (64 x 64 block, sample chunk): enough chunks for about two waves per
-            // SIMD over all bases, never less than 64 sample slices per chunk
+            // one wave per (64 x 64 block, sample chunk): as many chunks as fill, but do not exceed, the
+            // two waves per SIMD the kernel runs at (one wave more would cost a whole second round),
+            // never less than 64 sample slices per chunk
             const int64_t ng = gvq_large_groups(d), npairs = ng * (ng + 1) / 2;
-            int64_t chunks = (8LL * h->num_cu + npairs * n_blocks - 1) / (npairs * n_blocks);
+            int64_t chunks = (8LL * h->num_cu) / (npairs * n_blocks);
             if (chunks > (longest + 63) / 64) chunks = (longest + 63) / 64;
             if (chunks < 1) chunks = 1;
             h->P = (int)chunks;

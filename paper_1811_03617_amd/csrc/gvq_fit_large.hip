@@ -91,28 +91,36 @@ __global__ __launch_bounds__(256, 2) void moments_large_kernel(MomLargeArgs a)
         }
     };
 
+    // PF groups of 4 samples are in flight ahead of the one being multiplied (one group is 1024
+    // matrix-pipe cycles, a load from HBM takes several times that)
+    constexpr int PF = 4;
     for (int l = 0; l < a.L; ++l) {
         const void* g = a.grads.p[l];
-        float xa[4], xb[4], na[4], nb[4];
-        load_word(g, j0 + kk, ea, xa);
-        load_word(g, j0 + kk, eb, xb);
-        for (int64_t j = j0; j < j1; j += 4) {
-            load_word(g, j + 4 + kk, ea, na);   // one group of samples ahead; past the range: zeros
-            load_word(g, j + 4 + kk, eb, nb);
-            double da[4], db[4];
+        float xa[PF][4], xb[PF][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                da[c] = (double)xa[c];
-                db[c] = (double)xb[c];
-                ssum[c] += da[c];
+        for (int u = 0; u < PF; ++u) {
+            load_word(g, j0 + 4 * u + kk, ea, xa[u]);
+            load_word(g, j0 + 4 * u + kk, eb, xb[u]);
+        }
+        for (int64_t j = j0; j < j1; j += 4 * PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                double da[4], db[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    da[c] = (double)xa[u][c];
+                    db[c] = (double)xb[u][c];
+                    ssum[c] += da[c];
+                }
+                // this group's registers are free again: ask for the group PF further on (zeros past the range)
+                load_word(g, j + 4 * (u + PF) + kk, ea, xa[u]);
+                load_word(g, j + 4 * (u + PF) + kk, eb, xb[u]);
+#pragma unroll
+                for (int c1 = 0; c1 < 4; ++c1)
+#pragma unroll
+                    for (int c2 = 0; c2 < 4; ++c2)
+                        acc[c1][c2] = __builtin_amdgcn_mfma_f64_16x16x4f64(da[c1], db[c2], acc[c1][c2], 0, 0, 0);
             }
-#pragma unroll
-            for (int c1 = 0; c1 < 4; ++c1)
-#pragma unroll
-                for (int c2 = 0; c2 < 4; ++c2)
-                    acc[c1][c2] = __builtin_amdgcn_mfma_f64_16x16x4f64(da[c1], db[c2], acc[c1][c2], 0, 0, 0);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) { xa[c] = na[c]; xb[c] = nb[c]; }
         }
     }
 
