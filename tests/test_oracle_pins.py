@@ -406,3 +406,34 @@ def test_first_slice_sampling_mode():
     # fewer samples than dimensions: the covariance is rank deficient (rank <= L - 1)
     U, mu, eig = oracle.fit(grads[:4], d, k, offsets=offs, first_slice_only=True)
     assert np.all(np.abs(eig[:, 3:]) < 1e-13) and np.all(eig[:, 2] > 1e-3)
+
+
+# ---------------------------------------------------------------- long slices (Section 3: 768 in the paper's example)
+def test_long_slices_fit_equals_eigh_and_codec_round_trips():
+    """The oracle at slice lengths beyond 128: mean/covariance against numpy, eigenpairs against
+    numpy's symmetric solver (d = 160), and Eqs. (2)-(4) at the largest supported length with
+    k = d, where decompress(compress(x)) must give back x (plain numpy projections as the pin)."""
+    rng = np.random.default_rng(77)
+    d, k, M = 160, 12, 160 * 600 + 37
+    A = rng.standard_normal((d, 5))
+    fit = [(rng.standard_normal((M // d + 1, 5)) @ A.T + 0.1 * rng.standard_normal((M // d + 1, d))
+            ).astype(np.float32).reshape(-1)[:M] for _ in range(2)]
+    U, mu, eig, C = oracle.fit(fit, d, k, return_cov=True)
+    X = np.concatenate([g[: (M // d) * d].astype(np.float64).reshape(-1, d) for g in fit])
+    np.testing.assert_allclose(mu[0], X.mean(0), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(C[0], np.cov(X.T, bias=True), rtol=0, atol=1e-11 * eig[0][0])
+    w, V = np.linalg.eigh(C[0])
+    np.testing.assert_allclose(eig[0], w[::-1], rtol=0, atol=1e-10 * w[-1])
+    s = np.linalg.svd(U[0][:, :5].T @ V[:, ::-1][:, :5], compute_uv=False)
+    assert np.max(np.arccos(np.clip(s, -1, 1))) < 1e-6
+
+    d = oracle.MAX_D
+    M = d * 7 + 300                                  # a partial last slice
+    Q = np.linalg.qr(rng.standard_normal((d, d)))[0]
+    m = rng.standard_normal(d)
+    xs = [rng.standard_normal(M).astype(np.float32) for _ in range(3)]
+    ys = [oracle.compress(x, Q[None], m[None], 3) for x in xs]
+    xp = np.zeros((8, d)); xp.reshape(-1)[:M] = xs[1]
+    np.testing.assert_allclose(ys[1], (xp - m / 3) @ Q, rtol=0, atol=1e-12)      # Eq. (2) in plain numpy
+    out = oracle.decompress(oracle.aggregate(ys), Q[None], m[None], M)
+    np.testing.assert_allclose(out[: 7 * d], np.sum(xs, axis=0, dtype=np.float64)[: 7 * d], rtol=0, atol=1e-11)
