@@ -227,3 +227,93 @@ def test_fullsize_fit(name):
         for (i, j) in [(0, 0), (1, w.d - 1), (w.d // 2, w.d // 3)]:
             ref = oracle.cov_entry(sub, w.d, i, j, dtype=w.dtype)
             assert abs(C[bb][i, j] - ref) < 1e-11 * lam1
+
+
+@pytest.mark.parametrize("d,k,dtype", [(128, 16, "bf16"), (128, 32, "f32"), (768, 96, "f32")])
+def test_more_than_2_to_31_elements(d, k, dtype):
+    """Element and byte offsets beyond 2^31 / 2^32: one worker's gradient of 2^31 + 128 040 elements,
+    checked against the oracle on slice ranges at the start, around element 2^31 and at the ragged end."""
+    M = (1 << 31) + 128 * 1000 + 40
+    N = 3
+    rng = np.random.default_rng(d + k)
+    U = np.linalg.qr(rng.standard_normal((d, k)))[0][None]
+    mu = 0.05 * rng.standard_normal((1, d))
+    U32, mu32 = U.astype(np.float32), mu.astype(np.float32)
+    U64, mu64 = U32.astype(np.float64), mu32.astype(np.float64)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device=DEV).manual_seed(99)
+    g = torch.empty(M, device=DEV, dtype=tdt)
+    step = 1 << 28
+    for lo in range(0, M, step):                      # in pieces: randn of 2^31 floats at once is not needed
+        n = min(step, M - lo)
+        g[lo:lo + n] = torch.randn(n, device=DEV, generator=gen).to(tdt)
+    b = gvq.Basis(M, d, k, None, dtype)
+    b.import_(U32, mu32)
+    S = b.S
+    comp = torch.full((S * k,), float("nan"), device=DEV)
+    b.compress(g, N, comp)
+    out = torch.full((M,), float("nan"), device=DEV, dtype=torch.float32)
+    b.decompress(comp, out, "f32")
+    loss = torch.empty(1, device=DEV, dtype=torch.float64)
+    b.local_loss(g, N, loss)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(comp).all()) and bool(torch.isfinite(out).all())
+    mid = (1 << 31) // d
+    for (j0, j1) in [(0, 200), (mid - 150, mid + 150), (S - 300, S)]:
+        lo, hi = j0 * d, min(j1 * d, M)
+        gh = synth.to_numpy(g[lo:hi])
+        y = oracle.compress(gh, U64, mu64, N, dtype=dtype)
+        got = comp[j0 * k:j1 * k].cpu().numpy().reshape(-1, k)
+        assert_close(got, y, REL_TOL, f"compress slices [{j0},{j1})")
+        xh = oracle.decompress(got.astype(np.float64), U64, mu64, hi - lo)
+        assert_close(out[lo:hi].cpu().numpy(), xh, REL_TOL, f"decompress slices [{j0},{j1})")
+    # Eq. 6 over the whole gradient against float64 PyTorch from the library's own projections
+    ref = 0.0
+    chunk = (1 << 20)
+    Ut, mut = torch.from_numpy(U64[0]).to(DEV), torch.from_numpy(mu64[0]).to(DEV)
+    for s0 in range(0, S, chunk):
+        s1 = min(S, s0 + chunk)
+        x = torch.zeros((s1 - s0) * d, device=DEV, dtype=torch.float64)
+        n = min(s1 * d, M) - s0 * d
+        x[:n] = g[s0 * d:s0 * d + n].double()
+        xc = x.view(-1, d) - mut / N
+        r = xc - (xc @ Ut) @ Ut.T
+        if s1 == S and M % d:
+            r[-1, M % d:] = 0.0                         # only elements that exist count
+        ref += float((r * r).sum())
+    assert abs(float(loss[0]) - ref) <= 1e-4 * ref
+    b.close()
+
+
+@pytest.mark.parametrize("d,k", [(128, 8), (192, 8)])
+def test_fit_on_more_than_2_to_31_elements(d, k):
+    """The moment kernels' offsets beyond 2^31 elements: mean and covariance of one fp32 gradient of
+    2^31 + 128 040 elements against float64 PyTorch over every full slice."""
+    M = (1 << 31) + 128 * 1000 + 40
+    gen = torch.Generator(device=DEV).manual_seed(7)
+    g = torch.empty(M, device=DEV)
+    step = 1 << 28
+    for lo in range(0, M, step):
+        n = min(step, M - lo)
+        g[lo:lo + n] = torch.randn(n, device=DEV, generator=gen) + 0.25
+    g[(1 << 31) + 5: (1 << 31) + 5 + 3 * d] *= 100.0          # three slices beyond 2^31 that must be seen
+    full = M // d
+    s = torch.zeros(d, device=DEV, dtype=torch.float64)
+    G = torch.zeros(d, d, device=DEV, dtype=torch.float64)
+    chunk = 1 << 20
+    for s0 in range(0, full, chunk):
+        X = g[s0 * d:min(full, s0 + chunk) * d].double().view(-1, d)
+        s += X.sum(0)
+        G += X.T @ X
+    mu_ref = (s / full).cpu().numpy()
+    C_ref = (G / full).cpu().numpy() - np.outer(mu_ref, mu_ref)
+    b = gvq.Basis(M, d, k)
+    b.fit([g])
+    assert b.fit_status() >= 0
+    _, mu, eig = b.export()
+    C, n = b.export_cov()
+    b.close()
+    assert n[0] == full
+    np.testing.assert_allclose(mu[0], mu_ref, rtol=2e-7, atol=1e-9)
+    assert np.max(np.abs(C[0] - C_ref)) <= 1e-9 * np.max(np.abs(C_ref))
+    assert abs(eig[0].sum() - np.trace(C_ref)) <= 1e-9 * np.trace(C_ref)
