@@ -58,12 +58,13 @@ typedef enum {
     GVQ_ENOCONV = -7     /* gvq_fit_status: the eigensolver hit its sweep limit */
 } gvq_status_t;
 
-#define GVQ_MAX_D 1024 /* largest supported slice length */
+#define GVQ_MAX_D 1024      /* largest supported slice length */
+#define GVQ_MAX_BASES 65535 /* most bases per handle (the basis index is a grid dimension of the fit kernels) */
 
 /*
  * Create the codec state for gradients of n_elems (M >= 1) elements of grad_dtype, slice
  * length d in [2, GVQ_MAX_D], k in [1, d] kept components (the paper requires k < d; k = d
- * is accepted and makes the codec lossless).  block_slice_offsets: host array of
+ * is accepted and makes the codec lossless), n_blocks in [1, GVQ_MAX_BASES] bases.  block_slice_offsets: host array of
  * n_blocks+1 strictly increasing slice indices, first 0, last S; NULL means one basis for
  * the whole gradient (n_blocks must then be 1).  Allocates the device copies of U, mu,
  * eig and the fit scratch on the current device.  Section 2 (slicing; one compressor per

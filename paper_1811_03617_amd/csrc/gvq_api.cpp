@@ -74,7 +74,8 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
 {
     if (!out) return GVQ_EINVAL;
     *out = nullptr;
-    if (n_elems < 1 || d < 2 || d > GVQ_MAX_D || k < 1 || k > d || n_blocks < 1) return GVQ_EINVAL;
+    if (n_elems < 1 || d < 2 || d > GVQ_MAX_D || k < 1 || k > d || n_blocks < 1 || n_blocks > GVQ_MAX_BASES)
+        return GVQ_EINVAL;
     if (dtype != GVQ_F32 && dtype != GVQ_BF16) return GVQ_EINVAL;
     const int64_t S = (n_elems + d - 1) / d;
     if (!offs && n_blocks != 1) return GVQ_EINVAL;

@@ -45,6 +45,7 @@ def test_strerror_and_option_checks():
     (100, 16, 0, 1, None),      # k too small
     (100, 16, 17, 1, None),     # k > d
     (100, 16, 4, 2, None),      # several bases need offsets
+    (16 * 70000, 16, 4, 65536, list(range(65537))),   # more bases than a handle takes
     (160, 16, 4, 2, [0, 5, 9]),   # offsets do not end at S = 10
     (160, 16, 4, 2, [0, 5, 5]),   # not increasing
     (160, 16, 4, 2, [1, 5, 10]),  # does not start at 0
