@@ -208,3 +208,38 @@ def test_fit_degenerate_inputs():
     assert max_angle(U[0][:, :1].astype(np.float64), Uo[0][:, :1]) < ANGLE_TOL
     vn = (v / v.norm()).numpy().astype(np.float64)
     assert abs(abs(np.dot(U[0][:, 0], vn)) - 1) < 1e-6
+
+
+def test_thousands_of_small_bases():
+    """3000 bases of 24 slices each (the basis index is a grid dimension of the fit kernels, and the
+    codec's tiles straddle a basis boundary almost every time): fit and codec against the oracle."""
+    d, k, per, B = 16, 4, 24, 3000
+    M = d * per * B - 5
+    w = _wl(M, d, k, 2, 2, block_elems=d * per, rank=2, sigma=0.3)
+    assert w.n_blocks == B
+    offs = w.block_offsets()
+    fit = synth.fit_gradients(w, "cpu")
+    Uo, muo, eigo = oracle.fit([synth.to_numpy(g) for g in fit], d, k, offsets=offs)
+    b = gvq.Basis(M, d, k, offs)
+    b.fit([g.to(DEV) for g in fit])
+    assert 0 <= b.fit_status() < 40
+    U, mu, eig = b.export()
+    np.testing.assert_allclose(eig, eigo, rtol=0, atol=1e-10 * eigo.max())
+    np.testing.assert_allclose(mu, muo, rtol=2e-7, atol=1e-7 * np.abs(muo).max())
+    worst = max(max_angle(U[i][:, :2].astype(np.float64), Uo[i][:, :2]) for i in range(0, B, 37))
+    assert worst < ANGLE_TOL
+    # codec with the oracle's basis
+    U32, mu32 = Uo.astype(np.float32), muo.astype(np.float32)
+    b.import_(U32, mu32)
+    g = synth.worker_gradients(w, "cpu")[0]
+    comp = torch.empty(b.S * k, device=DEV)
+    out = torch.empty(M, device=DEV)
+    b.compress(g.to(DEV), 2, comp)
+    b.decompress(comp, out)
+    torch.cuda.synchronize()
+    y = oracle.compress(synth.to_numpy(g), U32.astype(np.float64), mu32.astype(np.float64), 2, offsets=offs)
+    assert_close(comp.cpu().numpy().reshape(-1, k), y, 1e-4, "compress")
+    xh = oracle.decompress(comp.cpu().numpy().reshape(-1, k).astype(np.float64), U32.astype(np.float64),
+                           mu32.astype(np.float64), M, offsets=offs)
+    assert_close(out.cpu().numpy(), xh, 1e-4, "decompress")
+    b.close()
