@@ -205,6 +205,7 @@ def _check_codec(w, out_dtype=None):
     (130 * 900 + 77, 130, 130, 2, "f32", 0),         # k = d: lossless
     (129 * 400 + 128, 129, 3, 2, "bf16", 129 * 100),
     (300, 512, 8, 2, "f32", 0),                      # a single partial slice
+    (256 * 10 * 40 + 77, 256, 24, 2, "f32", 256 * 10),   # 41 bases of 10 slices: every tile mostly empty
 ])
 @pytest.mark.parametrize("pipe", [1, 2], ids=["fp32-products", "bf16-split-products"])
 def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
