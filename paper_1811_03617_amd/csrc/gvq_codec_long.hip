@@ -84,6 +84,48 @@ __device__ __forceinline__ f4 load_x4(const LongArgs& a, bool row_ok, int64_t s,
     return v;
 }
 
+// Comps c0 .. c0+3 of slice s of the compressed output (plus the ring step's partial sum when
+// there is one); nothing past comp k.
+__device__ __forceinline__ void store_y4(const LongArgs& a, int64_t s, int c0, f4 v)
+{
+    if (c0 >= a.k) return;
+    float* Y = (float*)a.out;
+    const int64_t o = s * a.k + c0;
+    if ((a.k & 3) == 0) {
+        if (a.acc_in) v += *(const f4*)(a.acc_in + o);
+        *(f4*)(Y + o) = v;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
+    }
+}
+
+// Elements e0 .. e0+3 of slice s of the reconstructed gradient; `vec`: the whole tile lies inside
+// the gradient and d is a multiple of 4, so the word is stored whole.
+template <bool OUT_BF16>
+__device__ __forceinline__ void store_x4(const LongArgs& a, bool vec, int64_t s, int e0, f4 v)
+{
+    const int64_t idx = s * a.d + e0;
+    if (vec) {
+        if (OUT_BF16) {
+            u2 w2;
+            w2.x = pack_bf16x2(v[0], v[1]);
+            w2.y = pack_bf16x2(v[2], v[3]);
+            *(u2*)((unsigned short*)a.out + idx) = w2;
+        } else {
+            *(f4*)((float*)a.out + idx) = v;
+        }
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (e0 + r < a.d && idx + r < a.M) {
+            if (OUT_BF16) ((unsigned short*)a.out)[idx + r] = (unsigned short)f32_to_bf16_rne(v[r]);
+            else ((float*)a.out)[idx + r] = v[r];
+        }
+}
+
 // --------------------------------------------------------------------------------------
 // compress: D[comp][slice] += U[elem][comp] x[slice][elem].  For chunk c, word i (0..3) and
 // step j (0..3), lane (m, kk) of the A operand holds U[64c + w(i, kk) + j][16nt + m] and lane
@@ -250,25 +292,11 @@ __device__ __forceinline__ void compress_long_tile(const LongArgs& a, f4* Us, co
         }
         return;
     }
-    float* Y = (float*)a.out;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         if (!ok[t]) continue;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int c0 = 16 * nt + 4 * kk;
-            if (c0 >= a.k) continue;
-            const int64_t o = s[t] * a.k + c0;
-            f4 v = acc[t][nt];
-            if ((a.k & 3) == 0) {
-                if (a.acc_in) v += *(const f4*)(a.acc_in + o);
-                *(f4*)(Y + o) = v;
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
-            }
-        }
+        for (int nt = 0; nt < NT; ++nt) store_y4(a, s[t], 16 * nt + 4 * kk, acc[t][nt]);
     }
 }
 
@@ -401,25 +429,7 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
                 for (int et = 0; et < 4; ++et) {
                     const int e0 = c * LC + 16 * et + 4 * kk;
                     if (e0 >= a.d) continue;
-                    const f4 v = acc[t][et] + *(const f4*)(mus + e0);
-                    const int64_t idx = s[t] * a.d + e0;
-                    if (vec) {
-                        if (OUT_BF16) {
-                            u2 w2;
-                            w2.x = pack_bf16x2(v[0], v[1]);
-                            w2.y = pack_bf16x2(v[2], v[3]);
-                            *(u2*)((unsigned short*)a.out + idx) = w2;
-                        } else {
-                            *(f4*)((float*)a.out + idx) = v;
-                        }
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (e0 + r < a.d && idx + r < a.M) {
-                                if (OUT_BF16) ((unsigned short*)a.out)[idx + r] = (unsigned short)f32_to_bf16_rne(v[r]);
-                                else ((float*)a.out)[idx + r] = v[r];
-                            }
-                    }
+                    store_x4<OUT_BF16>(a, vec, s[t], e0, acc[t][et] + *(const f4*)(mus + e0));
                 }
             }
             if (c + 1 < a.nchunk) __syncthreads();
@@ -536,25 +546,11 @@ __device__ __forceinline__ void compress_split_tile(const LongArgs& a, u4* Us, c
         }
     }
 
-    float* Y = (float*)a.out;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
         if (!ok[t]) continue;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int c0 = 16 * nt + 4 * kk;
-            if (c0 >= a.k) continue;
-            const int64_t o = s[t] * a.k + c0;
-            f4 v = acc[t][nt];
-            if ((a.k & 3) == 0) {
-                if (a.acc_in) v += *(const f4*)(a.acc_in + o);
-                *(f4*)(Y + o) = v;
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (c0 + r < a.k) Y[o + r] = a.acc_in ? v[r] + a.acc_in[o + r] : v[r];
-            }
-        }
+        for (int nt = 0; nt < NT; ++nt) store_y4(a, s[t], 16 * nt + 4 * kk, acc[t][nt]);
     }
 }
 
@@ -676,25 +672,7 @@ __global__ __launch_bounds__(256, 2) void decompress_split_kernel(LongArgs a)
                 for (int et = 0; et < 4; ++et) {
                     const int e0 = c * LC + 16 * et + 4 * kk;
                     if (e0 >= a.d) continue;
-                    const f4 v = acc[t][et] + *(const f4*)(mus + e0);
-                    const int64_t idx = s[t] * a.d + e0;
-                    if (vec) {
-                        if (OUT_BF16) {
-                            u2 w2;
-                            w2.x = pack_bf16x2(v[0], v[1]);
-                            w2.y = pack_bf16x2(v[2], v[3]);
-                            *(u2*)((unsigned short*)a.out + idx) = w2;
-                        } else {
-                            *(f4*)((float*)a.out + idx) = v;
-                        }
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (e0 + r < a.d && idx + r < a.M) {
-                                if (OUT_BF16) ((unsigned short*)a.out)[idx + r] = (unsigned short)f32_to_bf16_rne(v[r]);
-                                else ((float*)a.out)[idx + r] = v[r];
-                            }
-                    }
+                    store_x4<OUT_BF16>(a, vec, s[t], e0, acc[t][et] + *(const f4*)(mus + e0));
                 }
             }
             if (c + 1 < a.nchunk) __syncthreads();
