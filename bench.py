@@ -20,6 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+FP64_MFMA_PEAK_TFLOPS = 78.6  # MI355X published fp64 matrix rate
 
 
 def main():
@@ -27,7 +28,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--workload", default="vgg16", help="a workload name, or \"all\" for one line per workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run gvq_aggregate with ONE input three times: a plain "
@@ -42,16 +43,28 @@ def main():
         sys.exit("bench.py: this build runs on ONE GPU only (the N workers are simulated as N "
                  "device buffers on it); --gpus above 1 is not supported.")
 
+    import torch
+
+    from paper_1811_03617_amd import WORKLOADS
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    # "all": one JSON line per workload (the table of the design doc from one command); the default is the
+    # headline workload alone, ONE line
+    names = list(WORKLOADS) if args.workload == "all" else [args.workload]
+    for name in names:
+        print(json.dumps(run_workload(name, args)), flush=True)
+
+
+def run_workload(name, args):
     import numpy as np
     import torch
 
     from paper_1811_03617_amd import WORKLOADS, gvq, synth
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = WORKLOADS[args.workload]
+    w = WORKLOADS[name]
     L = args.fit_gradients or w.L
     es = 2 if w.dtype == "bf16" else 4
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -190,8 +203,30 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "compress", "achieved": round(comp_bytes / comp_ms / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(comp_bytes / comp_ms / 1e6 / HBM_PEAK_GBS, 4),
-                     "algorithmic_bytes_per_launch": comp_bytes, "traffic": traffic},
+                     "algorithmic_bytes_per_launch": comp_bytes, "traffic": traffic,
+                     # the counters need the profiler around the process: this number is the committed
+                     # result of that run (command in the named file), not a measurement of this run
+                     "traffic_source": None if traffic is None else
+                     "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE/WRITE_SIZE runs, see profiles/*_hbm_traffic.md)"},
     }
+    # the basis refresh against its own roofline: d x d Gram sums on the fp64 matrix pipe (only the
+    # symmetric half of the 16 x 16 blocks is multiplied), input read once from HBM
+    if not args.skip_fit:
+        full = w.M // w.d
+        blocks16 = (w.d + 15) // 16
+        fit_flop = 2.0 * L * full * 256 * (blocks16 * (blocks16 + 1) // 2)
+        fit_in_bytes = float(L) * w.M * es
+        mfma_s, hbm_s = fit_flop / (FP64_MFMA_PEAK_TFLOPS * 1e12), fit_in_bytes / (HBM_PEAK_GBS * 1e9)
+        if mfma_s >= hbm_s:
+            res["fit"]["roofline"] = {"bound": "mfma", "achieved": round(fit_flop / fit_ms / 1e9, 2),
+                                      "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                      "frac": round(fit_flop / fit_ms / 1e9 / FP64_MFMA_PEAK_TFLOPS, 4),
+                                      "note": "whole refresh (moments + eigensolver) against the moments' flop"}
+        else:
+            res["fit"]["roofline"] = {"bound": "hbm", "achieved": round(fit_in_bytes / fit_ms / 1e6, 1),
+                                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": round(fit_in_bytes / fit_ms / 1e6 / HBM_PEAK_GBS, 4),
+                                      "note": "whole refresh (moments + eigensolver) against the input bytes"}
     # slices longer than 128 elements multiply on the bf16 matrix pipe (three products of bf16 terms per
     # fp32 product): should that ever take longer at its peak than the bytes take at the HBM peak, the
     # pipe is the roofline
@@ -233,8 +268,16 @@ def main():
                                "cores": threads, "kind": "oracle",
                                "sample": f"first {ns} of {S} slices of all {w.N} workers "
                                          f"({sample_bytes / 1e9:.2f} GB of gradient), {t_cpu:.1f} s"}
+        # the same oracle on ONE thread, on a sample sized for ~4 s
+        oracle.set_threads(1)
+        ns1 = int(min(S, max(1 << 10, ns * 4.0 / max(t_cpu, 1e-6) / max(threads, 1))))
+        t1 = run_oracle(ns1)
+        oracle.set_threads(threads)
+        res["cpu_baseline"]["value_1_thread"] = round(w.N * min(w.M, ns1 * w.d) * es / t1 / 1e9, 3)
+        res["cpu_baseline"]["sample_1_thread"] = f"first {ns1} slices, {t1:.1f} s"
     basis.close()
-    print(json.dumps(res), flush=True)
+    del workers, comps, total, out
+    return res
 
 
 if __name__ == "__main__":

@@ -73,10 +73,12 @@ typedef enum {
 int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blocks,
                      const int64_t* block_slice_offsets, gvq_dtype_t grad_dtype);
 
-/* Release the handle and its device memory.  Synchronises the device first. NULL is OK. */
+/* Release the handle (the state of Section 2's compressor: U, mu, eig) and its device memory.
+ * Synchronises the device first.  NULL is OK. */
 int gvq_basis_destroy(gvq_basis_t* h);
 
-/* S = ceil(M/d), or GVQ_EINVAL for a NULL handle. */
+/* S = ceil(M/d), the number of slices of Section 2 ("each gradient vector is cut into slices"), or
+ * GVQ_EINVAL for a NULL handle. */
 int64_t gvq_num_slices(const gvq_basis_t* h);
 
 /*
@@ -190,22 +192,25 @@ int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double
 int gvq_select_k(const gvq_basis_t* h, double lambda, int* k_out, void* stream);
 
 /*
- * Copy the basis to host arrays (any may be NULL): U float [B][d][k], mu float [B][d],
- * eig double [B][d].  Synchronises the device.  eig is all zero after gvq_basis_import.
+ * Checkpoint of the codec state that the PCA paragraph of Section 2 defines (the eigen matrix cut to
+ * its first k columns, the whitening vector, the eigenvalue vector): copy the basis to host arrays
+ * (any may be NULL): U float [B][d][k], mu float [B][d], eig double [B][d].  Synchronises the device.
+ * eig is all zero after gvq_basis_import.
  */
 int gvq_basis_export(const gvq_basis_t* h, float* U, float* mu, double* eig);
 
 /*
- * Host copy of the covariance matrices of the last fit, double [B][d][d] (what the
- * eigensolver was given), and of the per-basis sample counts int64 [B] (either may be
- * NULL).  Synchronises the device.  GVQ_ENOTFIT unless gvq_fit_basis ran on this handle.
+ * Diagnostics of the last fit (Section 2, PCA paragraph): host copy of the covariance matrices,
+ * double [B][d][d] (what the eigensolver was given), and of the per-basis sample counts, int64 [B],
+ * as the moment kernels counted the slices they took in (either may be NULL).  Synchronises the
+ * device.  GVQ_ENOTFIT unless gvq_fit_basis ran on this handle.
  */
 int gvq_basis_export_cov(const gvq_basis_t* h, double* cov, int64_t* n_samples);
 
 /*
- * Replace the basis by host arrays U float [B][d][k] and mu float [B][d] (checkpoint
- * restore; also lets a test inject a basis).  U is used as given: no orthonormality check.
- * Synchronous.
+ * Restore of that checkpoint: replace the basis by host arrays U float [B][d][k] and mu float [B][d]
+ * (the two parts of the state that Eqs. 2 and 4 use; also lets a test inject a basis).  U is used as
+ * given: no orthonormality check.  Synchronous.
  */
 int gvq_basis_import(gvq_basis_t* h, const float* U, const float* mu);
 
@@ -226,7 +231,14 @@ const char* gvq_strerror(int status);
  *             else products of two-term bf16 splits with fp32 accumulation (each product good to
  *             about 1e-5 of its magnitude, results within 1e-5 of the exact ones relative to the
  *             largest value, up to 2 times faster); 1 = always exact products; 2 = always the split.
- * Returns GVQ_EINVAL for unknown options or values out of range.
+ *   option 3: bit mask that sends every tile of a kernel family through its bounds-checked general loop
+ *             instead of the branch-free loop over whole tiles (1: fp32-pipe compress, 2: bf16-pipe
+ *             compress, 4: decompress); results are identical, for A/B timing;
+ *   option 4: pacing of the branch-free loop, -1 = each kernel's default: bit 0 = a wave waits for all its
+ *             memory work before it parks the next tile, bit 1 = also after a tile's matrix products,
+ *             bit 2 = the matrix products wait for the next tile's loads one by one.
+ * The options are plain process-wide variables read at launch time: set them while no other thread is
+ * inside a libgvq call.  Returns GVQ_EINVAL for unknown options or values out of range.
  */
 int gvq_set_option(int option, int value);
 

@@ -37,6 +37,8 @@ def lib():
         L.gvq_oracle_jacobi_eig.restype = i32
         L.gvq_oracle_moments.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i64, i64, dp, dp]
         L.gvq_oracle_moments.restype = i64
+        L.gvq_oracle_mean.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i64, i64, dp]
+        L.gvq_oracle_mean.restype = i64
         L.gvq_oracle_cov_entry.argtypes = [C.POINTER(vp), i32, i64, i32, i32, i64, i64, i32, i32]
         L.gvq_oracle_cov_entry.restype = C.c_double
         L.gvq_oracle_basis_from_cov.argtypes = [dp, i32, i32, dp, dp]
@@ -126,6 +128,16 @@ def moments(grads, d, dtype="f32", s0=0, s1=None):
     Cm = np.empty((d, d), dtype=np.float64)
     n = lib().gvq_oracle_moments(arr, len(keep), M, d, _DT[dtype], s0, s1, _dptr(mu), _dptr(Cm))
     return mu, Cm, n
+
+
+def mean(grads, d, dtype="f32", s0=0, s1=None):
+    """Sample mean over the full slices [s0, s1) of every gradient (the mean of `moments`, on its own)."""
+    keep, arr, M = _grad_ptrs(grads, dtype)
+    if s1 is None:
+        s1 = M // d
+    mu = np.empty(d, dtype=np.float64)
+    lib().gvq_oracle_mean(arr, len(keep), M, d, _DT[dtype], s0, s1, _dptr(mu))
+    return mu
 
 
 def cov_entry(grads, d, a, b, dtype="f32", s0=0, s1=None):

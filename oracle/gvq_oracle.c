@@ -230,6 +230,27 @@ int64_t gvq_oracle_moments(const void *const *grads, int L, int64_t M, int d, in
     return n;
 }
 
+/* The sample mean alone (the "whitening vector" of the PCA paragraph of Section 2) over the same
+ * sample set as gvq_oracle_moments: every full slice [s0, s1) of each of the L gradients.  For
+ * checks at sizes where the whole covariance is too slow.  Returns the number of samples. */
+int64_t gvq_oracle_mean(const void *const *grads, int L, int64_t M, int d, int dtype, int64_t s0,
+                        int64_t s1, double *mu)
+{
+    int64_t full = M / d;
+    if (s1 > full) s1 = full;
+    int64_t per = s1 > s0 ? s1 - s0 : 0;
+    int64_t n = per * (int64_t)L;
+    for (int e = 0; e < d; ++e) {
+        double acc = 0.0;
+        for (int l = 0; l < L; ++l) {
+#pragma omp parallel for schedule(static) reduction(+ : acc)
+            for (int64_t j = s0; j < s1; ++j) acc += load_elem(grads[l], dtype, j * d + e);
+        }
+        mu[e] = n > 0 ? acc / (double)n : 0.0;
+    }
+    return n;
+}
+
 /* One entry (a,b) of the covariance above, computed on its own (for spot checks at
  * sizes where the whole matrix is too slow): two passes over the samples. */
 double gvq_oracle_cov_entry(const void *const *grads, int L, int64_t M, int d, int dtype,

@@ -14,6 +14,8 @@ static thread_local char g_msg[320];
 static int g_wg_per_cu = 0;
 static int g_run_tiles = 0;
 static int g_long_mode = 0;
+static int g_no_fast = 0;
+static int g_pace = -1;
 
 int gvq_hip_fail(hipError_t e, const char* what)
 {
@@ -25,6 +27,8 @@ int gvq_hip_fail(hipError_t e, const char* what)
 int gvq_opt_wg_per_cu() { return g_wg_per_cu; }
 int gvq_opt_run_tiles() { return g_run_tiles; }
 int gvq_opt_long_mode() { return g_long_mode; }
+int gvq_opt_no_fast() { return g_no_fast; }
+int gvq_opt_pace() { return g_pace; }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -52,6 +56,8 @@ int gvq_set_option(int option, int value)
     if (option == 0 && value >= 0 && value <= 64) { g_wg_per_cu = value; return GVQ_OK; }
     if (option == 1 && value >= 0) { g_run_tiles = value; return GVQ_OK; }
     if (option == 2 && value >= 0 && value <= 2) { g_long_mode = value; return GVQ_OK; }
+    if (option == 3 && value >= 0 && value <= 7) { g_no_fast = value; return GVQ_OK; }
+    if (option == 4 && value >= -1 && value <= 7) { g_pace = value; return GVQ_OK; }
     return GVQ_EINVAL;
 }
 
@@ -59,9 +65,14 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_jac, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_nsamp, h->d_jac, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
+    for (gvq_plan& pl : h->plan) {
+        if (pl.d_sup_tile) (void)hipFree(pl.d_sup_tile);
+        if (pl.d_sup_basis) (void)hipFree(pl.d_sup_basis);
+        if (pl.d_rest) (void)hipFree(pl.d_rest);
+    }
     free(h->h_offs);
     free(h->h_ltile);
     delete h;
@@ -170,6 +181,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             TRY(hipMalloc((void**)&h->d_part2, sizeof(double) * B * (size_t)((h->P + 31) / 32) * width));
         }
         TRY(hipMalloc((void**)&h->d_mom, sizeof(double) * B * W));
+        TRY(hipMalloc((void**)&h->d_nsamp, sizeof(unsigned long long) * B));
         TRY(hipMalloc((void**)&h->d_sweeps, sizeof(int) * B));
         TRY(hipMalloc((void**)&h->d_ksel, sizeof(int) * B));
         TRY(hipMalloc((void**)&h->d_loss_slice, sizeof(float) * (size_t)S));
@@ -193,6 +205,8 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             if (e != hipSuccess) { rc = gvq_hip_fail(e, "tile_block upload"); goto fail; }
         }
         TRY(hipMemset(h->d_eig, 0, sizeof(double) * B * d));
+        rc = gvq_build_plans(h);
+        if (rc != GVQ_OK) goto fail;
     }
 #undef TRY
     *out = h;
@@ -374,12 +388,8 @@ int gvq_basis_export_cov(const gvq_basis_t* h, double* cov, int64_t* n_samples)
     const size_t B = (size_t)h->B;
     if (cov) GVQ_HIP(hipMemcpy(cov, h->d_cov, sizeof(double) * B * h->d * h->d, hipMemcpyDeviceToHost));
     if (n_samples) {
-        const int64_t full = h->M / h->d;
-        for (size_t b = 0; b < B; ++b) {
-            int64_t hi = h->h_offs[b + 1] < full ? h->h_offs[b + 1] : full;
-            int64_t cnt = hi > h->h_offs[b] ? hi - h->h_offs[b] : 0;
-            n_samples[b] = (h->fit_first_slice ? (cnt > 0 ? 1 : 0) : cnt) * h->fit_L;
-        }
+        static_assert(sizeof(unsigned long long) == sizeof(int64_t), "sample counters are copied as they are");
+        GVQ_HIP(hipMemcpy(n_samples, h->d_nsamp, sizeof(int64_t) * B, hipMemcpyDeviceToHost));
     }
     return GVQ_OK;
 }

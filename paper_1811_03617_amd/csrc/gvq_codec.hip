@@ -15,6 +15,189 @@
 #include "gvq_device.h"
 
 // --------------------------------------------------------------------------------------
+// Fast phase shared by the register-resident kernels.
+//
+// The bounds-checked loops further down serve every tile, but their branches (partial tiles,
+// slices of two bases in one tile, basis reloads) make the compiler's wait-count bookkeeping give
+// up: it then waits for *everything* in flight at the top of every tile -- the prefetched next
+// tile and the stores just issued -- and a wave has nothing in flight while it multiplies.  So the
+// bulk of the work, whole tiles of one basis, runs in a loop without a single branch around a
+// memory instruction: every load and store is unconditional (lanes with nothing to do repeat the
+// last valid address; duplicate stores write the same bytes), the basis is loaded outside the
+// tile loop and waited for explicitly, and the next super-tile's loads are issued right after the
+// current one is parked in LDS.  The compiler then counts exactly: the wait before parking a tile
+// leaves the previous tile's stores in flight.
+// A super-tile is 2048 consecutive gradient elements (128/D 16-slice tiles): 8 loads of 128 bits
+// per lane whatever the slice length, so short slices move as many bytes per loop trip as long ones.
+// --------------------------------------------------------------------------------------
+// MANY: the handle has several bases and the super-tiles come from its tables; otherwise they are
+// consecutive and all of basis 0.  G: 16-slice tiles per super-tile.
+template <int G, bool MANY>
+__device__ __forceinline__ int64_t super_tile(const CodecArgs& a, int64_t p)
+{
+    if constexpr (MANY) return uniform_load(a.sup_tile + p);
+    else return a.sup_first + p * G;
+}
+template <bool MANY>
+__device__ __forceinline__ int super_basis(const CodecArgs& a, int64_t p)
+{
+    if constexpr (MANY) return uniform_load(a.sup_basis + p);
+    else return 0;
+}
+
+// NSO = 128-bit result words per lane and super-tile: ceil(8 k / D), a template value so that the
+// stores can be counted (YS picks it: the largest possible number, G * NT, shifted right by YS).
+template <int D, int NT, bool BF16, int VAR, int YS, bool MANY>
+__device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
+{
+    constexpr int G = 128 / D;                    // 16-slice tiles per super-tile
+    constexpr int CPS = D / 4;                    // fp32 128-bit chunks per slice
+    constexpr int EPL = BF16 ? 8 : 4;             // elements per 128-bit global load
+    constexpr int LCPS = D / EPL;                 // load chunks per slice
+    constexpr int NL = 2048 / EPL / 64;           // loads per lane per super-tile
+    constexpr int NQ = CPS / 4;
+    constexpr int KC = 4 * NT;                    // 128-bit chunks per slice of the padded result tile
+    constexpr int NSO = ((G * NT) >> YS) > 0 ? ((G * NT) >> YS) : 1;
+    constexpr bool RING = (VAR & 4) != 0;
+
+    SuperIter it;
+    if (!it.init(a.n_super, a.run_tiles)) return;
+
+    const int lane = threadIdx.x & 63, n_ = lane & 15, kk = lane >> 4;
+    const int kc = a.k >> 2, cnt = G * TILE_SLICES * kc;   // result words of a super-tile
+    int so_slot[NSO], so_off[NSO];
+#pragma unroll
+    for (int r = 0; r < NSO; ++r) {
+        int gi = r * 64 + lane;
+        if (gi > cnt - 1) gi = cnt - 1;
+        const int s = gi / kc, c = gi - s * kc;
+        so_slot[r] = s * KC + (c ^ swz<16 * NT>(s & 15));
+        so_off[r] = 4 * gi;
+    }
+    const int lc = lane % LCPS;
+    int in_slot[NL];
+#pragma unroll
+    for (int r = 0; r < NL; ++r) {
+        const int row = (r * 64 + lane) / LCPS;
+        in_slot[r] = row * CPS + ((BF16 ? 2 * lc : lc) ^ swz<D>(row & 15));
+    }
+
+    f4 uf[NQ][NT];
+    float mun[EPL];
+    auto load_basis = [&](int b) {
+        const f4* Up = a.Upack + (size_t)b * (NQ * NT * 64) + lane;
+        const float* mub = a.mu + (size_t)b * D;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) uf[q][nt] = Up[(q * NT + nt) * 64];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) mun[i] = mub[lc * EPL + i] / a.n_workers;
+    };
+
+    u4 regs[NL];
+    f4 prev[RING ? NSO : 1];
+    auto load_super = [&](int64_t t0) {
+        const char* base = (const char*)a.in + t0 * (int64_t)(TILE_SLICES * D) * (BF16 ? 2 : 4) + lane * 16;
+#pragma unroll
+        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * 1024));
+        if constexpr (RING) {
+            const float* pin = a.acc_in + t0 * TILE_SLICES * a.k;
+#pragma unroll
+            for (int r = 0; r < NSO; ++r) prev[r] = stream_load((const f4*)(pin + so_off[r]));
+        }
+    };
+
+    int64_t cur = it.p;
+    int b = super_basis<MANY>(a, cur);
+    load_super(super_tile<G, MANY>(a, cur));
+    for (;;) {
+        load_basis(b);
+        drain_memory();
+        int nb;
+        do {
+            const int64_t t0 = super_tile<G, MANY>(a, cur);
+            const bool more = it.advance();
+            const int64_t nxt = more ? it.p : cur;
+            nb = more ? super_basis<MANY>(a, nxt) : -1;
+            const int64_t tn = super_tile<G, MANY>(a, nxt);
+
+            if (a.pace & 1) drain_memory();
+            // park the super-tile in LDS as fp32, minus mu/N
+            wave_lds_sync();
+#pragma unroll
+            for (int r = 0; r < NL; ++r) {
+                const u4 v = regs[r];
+                if (BF16) {
+                    f4 lo = {bf16_to_f32(v.x & 0xffffu) - mun[0], bf16_to_f32(v.x >> 16) - mun[1],
+                             bf16_to_f32(v.y & 0xffffu) - mun[2], bf16_to_f32(v.y >> 16) - mun[3]};
+                    f4 hi = {bf16_to_f32(v.z & 0xffffu) - mun[4 % EPL], bf16_to_f32(v.z >> 16) - mun[5 % EPL],
+                             bf16_to_f32(v.w & 0xffffu) - mun[6 % EPL], bf16_to_f32(v.w >> 16) - mun[7 % EPL]};
+                    lds[in_slot[r]] = lo;
+                    lds[in_slot[r] ^ 1] = hi;
+                } else {
+                    f4 x = {__uint_as_float(v.x) - mun[0], __uint_as_float(v.y) - mun[1],
+                            __uint_as_float(v.z) - mun[2], __uint_as_float(v.w) - mun[3]};
+                    lds[in_slot[r]] = x;
+                }
+            }
+            f4 pv[RING ? NSO : 1];
+            if constexpr (RING) {
+#pragma unroll
+                for (int r = 0; r < NSO; ++r) pv[r] = prev[r];
+            }
+            load_super(tn);   // the next super-tile (or this one again, unused, when there is none)
+            wave_lds_sync();
+            f4 x[G][NQ];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) x[g][q] = lds[(g * 16 + n_) * CPS + ((4 * q + kk) ^ swz<D>(n_))];
+            f4 acc[G][NT];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[g][nt] = f4{0.f, 0.f, 0.f, 0.f};
+            __builtin_amdgcn_s_setprio(3);
+            // NQ * G = 8 = NL groups of products; with pacing, group i waits for load i of the next super-tile
+            static_for<0, NQ * G>([&](auto ic) {
+                constexpr int i = decltype(ic)::value, q = i / G, g = i % G;
+                if constexpr (NQ * G == NL) {
+                    if (a.pace & 4) wait_vmem_at_most<NL - 1 - i + (RING ? NSO : 0)>();
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[g][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[g][q][j], acc[g][nt], 0, 0, 0);
+            });
+            __builtin_amdgcn_s_setprio(0);
+            if (a.pace & 2) drain_memory();
+            // the result tiles leave through the same LDS region (every x is in registers by now) as
+            // full-width stores in memory order
+            wave_lds_sync();
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    lds[(g * 16 + n_) * KC + ((4 * nt + kk) ^ swz<16 * NT>(n_))] = acc[g][nt];
+            wave_lds_sync();
+            float* o = (float*)a.out + t0 * TILE_SLICES * a.k;
+#pragma unroll
+            for (int r = 0; r < NSO; ++r) {
+                f4 v = lds[so_slot[r]];
+                if constexpr (RING) v += pv[r];
+                stream_store((f4*)(o + so_off[r]), v);
+            }
+            cur = nxt;
+        } while (nb == b);
+        if (nb < 0) break;
+        b = nb;
+    }
+    drain_memory();
+}
+
+// --------------------------------------------------------------------------------------
 // compress, MFMA path.  D in {16,32,64,128}, NT = ceil(k/16) in {1,2}.
 //
 // Per 16-slice tile a wave loads 128-bit words in memory order (fully coalesced: the tile
@@ -27,7 +210,7 @@
 // The contraction index may be visited in any order as long as U follows: MFMA step
 // (q, j) multiplies elements e = 4*(4q + kk) + j, kk = l/16.
 // --------------------------------------------------------------------------------------
-template <int D, int NT, bool BF16, int VAR, bool LOSS>
+template <int D, int NT, bool BF16, int VAR, bool LOSS, int YS>
 __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel(CodecArgs a)
 {
     constexpr int CPS = D / 4;                    // fp32 128-bit chunks per slice
@@ -40,14 +223,20 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
 
     constexpr int KC = 4 * NT;                    // 128-bit chunks per slice of the padded result tile
 
-    __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
+    __shared__ f4 lds_all[WAVES_PER_WG][512];     // one super-tile of the fast phase (8 KB per wave)
     __shared__ f4 ldso_all[WAVES_PER_WG][TILE_SLICES * KC];
     const int lane = threadIdx.x & 63;
     f4* lds = lds_all[threadIdx.x >> 6];
     f4* ldso = ldso_all[threadIdx.x >> 6];
 
-    TileIter it;
-    if (!init_tiles(it, a)) return;
+    if constexpr (!LOSS) {
+        if (a.sup_tile) compress_fast_phase<D, NT, BF16, VAR, YS, true>(a, lds);
+        else compress_fast_phase<D, NT, BF16, VAR, YS, false>(a, lds);
+    }
+
+    // ---- general phase: the tiles the fast phase leaves out, every check in place ----------
+    RestIter it;
+    if (!it.init(a)) return;
 
     const int n_ = lane & 15, kk = lane >> 4;
     // result tile in memory order: 16 slices x k floats, contiguous; this lane's 128-bit pieces
@@ -303,7 +492,139 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
 // --------------------------------------------------------------------------------------
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
-template <int D, int NT, bool ACC>
+// Fast phase of the bf16-pipe compress (see compress_fast_phase).  A super-tile is G2 = 2 (D = 128) or 4
+// 16-slice tiles: 8 loads of 128 bits per lane at D >= 64, 4 at D = 32.
+template <int D> constexpr int bf16_super_tiles() { return D == 128 ? 2 : 4; }
+
+template <int D, int NT, bool ACC, int YS, bool MANY>
+__device__ __forceinline__ void compress_bf16_fast_phase(const CodecArgs& a, u4* lds)
+{
+    constexpr int G = bf16_super_tiles<D>();
+    constexpr int C8 = D / 8, NST = D / 32, KC = 4 * NT;
+    constexpr int NL = G * TILE_SLICES * C8 / 64;
+    constexpr int NSO = ((G * NT) >> YS) > 0 ? ((G * NT) >> YS) : 1;
+    f4* ldsf = (f4*)lds;
+
+    SuperIter it;
+    if (!it.init(a.n_super, a.run_tiles)) return;
+
+    const int lane = threadIdx.x & 63, n_ = lane & 15, kk = lane >> 4;
+    const int kc = a.k >> 2, cnt = G * TILE_SLICES * kc;
+    int so_slot[NSO], so_off[NSO];
+#pragma unroll
+    for (int r = 0; r < NSO; ++r) {
+        int gi = r * 64 + lane;
+        if (gi > cnt - 1) gi = cnt - 1;
+        const int s = gi / kc, c = gi - s * kc;
+        so_slot[r] = s * KC + (c ^ swz<16 * NT>(s & 15));
+        so_off[r] = 4 * gi;
+    }
+    int in_slot[NL];
+#pragma unroll
+    for (int r = 0; r < NL; ++r) {
+        const int g = r * 64 + lane, row = g / C8, c = g % C8;
+        in_slot[r] = row * C8 + (c ^ swz<D / 2>(row & 15));
+    }
+
+    u4 ua[NST][3][NT];
+    f4 bias[NT];
+    auto load_basis = [&](int b) {
+        const u4* Up = (const u4*)a.Upack + (size_t)b * (NST * 3 * NT * 64) + lane;
+#pragma unroll
+        for (int st = 0; st < NST; ++st)
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) ua[st][p][nt] = Up[((st * 3 + p) * NT + nt) * 64];
+        const f4* um = (const f4*)(a.Umu + (size_t)b * 16 * NT) + kk;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) bias[nt] = um[4 * nt] / a.n_workers;
+    };
+    u4 regs[NL];
+    f4 prev[ACC ? NSO : 1];
+    auto load_super = [&](int64_t t0) {
+        const char* base = (const char*)a.in + t0 * (int64_t)(TILE_SLICES * D) * 2 + lane * 16;
+#pragma unroll
+        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * 1024));
+        if constexpr (ACC) {
+            const float* pin = a.acc_in + t0 * TILE_SLICES * a.k;
+#pragma unroll
+            for (int r = 0; r < NSO; ++r) prev[r] = stream_load((const f4*)(pin + so_off[r]));
+        }
+    };
+
+    int64_t cur = it.p;
+    int b = super_basis<MANY>(a, cur);
+    load_super(super_tile<G, MANY>(a, cur));
+    for (;;) {
+        load_basis(b);
+        drain_memory();
+        int nb;
+        do {
+            const int64_t t0 = super_tile<G, MANY>(a, cur);
+            const bool more = it.advance();
+            const int64_t nxt = more ? it.p : cur;
+            nb = more ? super_basis<MANY>(a, nxt) : -1;
+            const int64_t tn = super_tile<G, MANY>(a, nxt);
+
+            if (a.pace & 1) drain_memory();
+            wave_lds_sync();
+#pragma unroll
+            for (int r = 0; r < NL; ++r) lds[in_slot[r]] = regs[r];
+            f4 pv[ACC ? NSO : 1];
+            if constexpr (ACC) {
+#pragma unroll
+                for (int r = 0; r < NSO; ++r) pv[r] = prev[r];
+            }
+            load_super(tn);
+            wave_lds_sync();
+            u4 xb[G][NST];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int st = 0; st < NST; ++st) xb[g][st] = lds[(g * 16 + n_) * C8 + ((4 * st + kk) ^ swz<D / 2>(n_))];
+            f4 acc[G][NT];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[g][nt] = -bias[nt];
+            __builtin_amdgcn_s_setprio(3);
+            // NST * G = NL groups of products; with pacing, group i waits for load i of the next super-tile
+            static_for<0, NST * G>([&](auto ic) {
+                constexpr int i = decltype(ic)::value, st = i / G, g = i % G;
+                if (a.pace & 4) wait_vmem_at_most<NL - 1 - i + (ACC ? NSO : 0)>();
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[g][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf8, ua[st][p][nt]), __builtin_bit_cast(bf8, xb[g][st]), acc[g][nt], 0, 0, 0);
+            });
+            __builtin_amdgcn_s_setprio(0);
+            if (a.pace & 2) drain_memory();
+            wave_lds_sync();   // every xb is in registers: the region now takes the result tiles
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    ldsf[(g * 16 + n_) * KC + ((4 * nt + kk) ^ swz<16 * NT>(n_))] = acc[g][nt];
+            wave_lds_sync();
+            float* o = (float*)a.out + t0 * TILE_SLICES * a.k;
+#pragma unroll
+            for (int r = 0; r < NSO; ++r) {
+                f4 v = ldsf[so_slot[r]];
+                if constexpr (ACC) v += pv[r];
+                stream_store((f4*)(o + so_off[r]), v);
+            }
+            cur = nxt;
+        } while (nb == b);
+        if (nb < 0) break;
+        b = nb;
+    }
+    drain_memory();
+}
+
+template <int D, int NT, bool ACC, int YS>
 __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs a)
 {
     constexpr int C8 = D / 8;                        // 128-bit chunks (8 bf16) per slice
@@ -312,11 +633,16 @@ __global__ __launch_bounds__(WG_THREADS, 2) void compress_bf16_kernel(CodecArgs 
     constexpr int NST = D / 32;                      // MFMA steps per tile
     constexpr int64_t TILE_ELEMS = (int64_t)TILE_SLICES * D;
 
-    __shared__ u4 lds_all[WAVES_PER_WG][TILE_SLICES * C8];
+    __shared__ u4 lds_all[WAVES_PER_WG][512];        // one super-tile of the fast phase (8 KB per wave)
     const int lane = threadIdx.x & 63;
     u4* lds = lds_all[threadIdx.x >> 6];
-    TileIter it;
-    if (!init_tiles(it, a)) return;
+
+    if (a.sup_tile) compress_bf16_fast_phase<D, NT, ACC, YS, true>(a, lds);
+    else compress_bf16_fast_phase<D, NT, ACC, YS, false>(a, lds);
+
+    // ---- general phase: the tiles the fast phase leaves out, every check in place ----------
+    RestIter it;
+    if (!it.init(a)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const bool loads = lane < TILE_LOADS;            // false only for the upper lanes at D = 32
 
@@ -464,6 +790,144 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
     }
 }
 
+// Fast phase of decompress (see compress_fast_phase): per super-tile the compressed rows arrive in
+// memory order (NY = ceil(8 k / D) full-width loads per lane, a template value through YS), are
+// transposed through LDS into the B operand, multiplied, and the 2048 reconstructed elements leave
+// through the same LDS region as 8 full-width stores per lane (4 for bf16 output), mu added on the
+// way out.  Nothing is conditional.
+template <int D, int NQ, bool OUT_BF16, int YS, bool MANY>
+__device__ __forceinline__ void decompress_fast_phase(const CodecArgs& a, f4* lds)
+{
+    constexpr int G = 128 / D, ET = D / 16, CPS = D / 4, KC = 4 * NQ;
+    constexpr int NY = ((G * NQ) >> YS) > 0 ? ((G * NQ) >> YS) : 1;
+    constexpr int EPS = OUT_BF16 ? 8 : 4;            // elements per 128-bit store
+    constexpr int SCPS = D / EPS;                    // store chunks per slice
+    constexpr int NS = 2048 / EPS / 64;              // stores per lane per super-tile
+
+    SuperIter it;
+    if (!it.init(a.n_super, a.run_tiles)) return;
+
+    const int lane = threadIdx.x & 63, n_ = lane & 15, kk = lane >> 4;
+    const float* Y = (const float*)a.in;
+    const int kc = a.k >> 2, cnt = G * TILE_SLICES * kc;   // 128-bit words of a super-tile's input
+    int si_slot[NY], si_off[NY];
+#pragma unroll
+    for (int r = 0; r < NY; ++r) {
+        int gi = r * 64 + lane;
+        if (gi > cnt - 1) gi = cnt - 1;
+        const int s = gi / kc, c = gi - s * kc;
+        si_slot[r] = s * KC + (c ^ swz<16 * NQ>(s & 15));
+        si_off[r] = 4 * gi;
+    }
+    const int sc = lane % SCPS;                      // this lane's store chunk within a slice
+    int out_slot[NS];
+#pragma unroll
+    for (int r = 0; r < NS; ++r) {
+        const int row = (r * 64 + lane) / SCPS;
+        out_slot[r] = row * CPS + ((OUT_BF16 ? 2 * sc : sc) ^ swz<D>(row & 15));
+    }
+    bool col_ok[NQ];                                 // padded columns of the input tile hold whatever was there
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) col_ok[q] = 4 * q + kk < kc;
+
+    f4 uf[ET][NQ];
+    float mul[EPS];
+    auto load_basis = [&](int b) {
+        const f4* Up = a.Upack + (size_t)b * (ET * NQ * 64) + lane;
+        const float* mub = a.mu + (size_t)b * D + sc * EPS;
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) uf[et][q] = Up[(et * NQ + q) * 64];
+#pragma unroll
+        for (int i = 0; i < EPS; ++i) mul[i] = mub[i];
+    };
+    f4 y[NY];
+    auto load_super = [&](int64_t t0) {
+        const float* p = Y + t0 * TILE_SLICES * a.k;
+#pragma unroll
+        for (int r = 0; r < NY; ++r) y[r] = stream_load((const f4*)(p + si_off[r]));
+    };
+
+    int64_t cur = it.p;
+    int b = super_basis<MANY>(a, cur);
+    load_super(super_tile<G, MANY>(a, cur));
+    for (;;) {
+        load_basis(b);
+        drain_memory();
+        int nb;
+        do {
+            const int64_t t0 = super_tile<G, MANY>(a, cur);
+            const bool more = it.advance();
+            const int64_t nxt = more ? it.p : cur;
+            nb = more ? super_basis<MANY>(a, nxt) : -1;
+            const int64_t tn = super_tile<G, MANY>(a, nxt);
+
+            if (a.pace & 1) drain_memory();
+            wave_lds_sync();
+#pragma unroll
+            for (int r = 0; r < NY; ++r) lds[si_slot[r]] = y[r];
+            load_super(tn);
+            wave_lds_sync();
+            f4 yc[G][NQ];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const f4 v = lds[(g * 16 + n_) * KC + ((4 * q + kk) ^ swz<16 * NQ>(n_))];
+                    yc[g][q] = col_ok[q] ? v : f4{0.f, 0.f, 0.f, 0.f};
+                }
+            f4 acc[G][ET];
+            __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int et = 0; et < ET; ++et) acc[g][et] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int et = 0; et < ET; ++et)
+                            acc[g][et] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[et][q][jj], yc[g][q][jj], acc[g][et], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+            if (a.pace & 2) drain_memory();
+            wave_lds_sync();   // every yc is in registers: the region now takes the result
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int et = 0; et < ET; ++et) lds[(g * 16 + n_) * CPS + ((4 * et + kk) ^ swz<D>(n_))] = acc[g][et];
+            wave_lds_sync();
+            char* o = (char*)a.out + (t0 * (int64_t)(TILE_SLICES * D)) * (OUT_BF16 ? 2 : 4) + lane * 16;
+#pragma unroll
+            for (int r = 0; r < NS; ++r) {
+                if (OUT_BF16) {
+                    f4 v0 = lds[out_slot[r]], v1 = lds[out_slot[r] ^ 1];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v0[i] += mul[i];
+                        v1[i] += mul[(4 + i) % EPS];
+                    }
+                    const u4 pk = {pack_bf16x2(v0[0], v0[1]), pack_bf16x2(v0[2], v0[3]),
+                                   pack_bf16x2(v1[0], v1[1]), pack_bf16x2(v1[2], v1[3])};
+                    stream_store((u4*)(o + r * 1024), pk);
+                } else {
+                    f4 v = lds[out_slot[r]];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] += mul[i];
+                    stream_store((f4*)(o + r * 1024), v);
+                }
+            }
+            cur = nxt;
+        } while (nb == b);
+        if (nb < 0) break;
+        b = nb;
+    }
+    drain_memory();
+}
+
 // --------------------------------------------------------------------------------------
 // decompress, MFMA path.  D in {16,32,64,128}, NQ = ceil(k/16) in {1,2}.
 // A = U tile (16 elements x 4 comps), B = Y (4 comps x 16 slices): lane (n = l%16, kk = l/16)
@@ -473,7 +937,7 @@ __global__ __launch_bounds__(256) void compress_generic_kernel(CodecArgs a)
 // it goes through the wave's LDS region (same swizzle as compress) and leaves as
 // full-width 128-bit stores in memory order.
 // --------------------------------------------------------------------------------------
-template <int D, int NQ, bool OUT_BF16>
+template <int D, int NQ, bool OUT_BF16, int YS>
 __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArgs a)
 {
     constexpr int ET = D / 16;
@@ -486,13 +950,18 @@ __global__ __launch_bounds__(WG_THREADS, 2) void decompress_mfma_kernel(CodecArg
 
     constexpr int KC = 4 * NQ;                       // 128-bit chunks per slice of the padded input tile
 
-    __shared__ f4 lds_all[WAVES_PER_WG][TILE_SLICES * CPS];
+    __shared__ f4 lds_all[WAVES_PER_WG][512];        // one super-tile of the fast phase (8 KB per wave)
     __shared__ f4 ldsi_all[WAVES_PER_WG][TILE_SLICES * KC];
     const int lane = threadIdx.x & 63;
     f4* lds = lds_all[threadIdx.x >> 6];
     f4* ldsi = ldsi_all[threadIdx.x >> 6];
-    TileIter it;
-    if (!init_tiles(it, a)) return;
+
+    if (a.sup_tile) decompress_fast_phase<D, NQ, OUT_BF16, YS, true>(a, lds);
+    else decompress_fast_phase<D, NQ, OUT_BF16, YS, false>(a, lds);
+
+    // ---- general phase: the tiles the fast phase leaves out, every check in place ----------
+    RestIter it;
+    if (!it.init(a)) return;
     const int n_ = lane & 15, kk = lane >> 4;
     const float* Y = (const float*)a.in;
     const bool vec = (a.k & 3) == 0;
@@ -817,7 +1286,89 @@ static CodecArgs make_args(const gvq_basis* h, const void* in, void* out, int n_
     a.acc_in = nullptr;
     a.seg_begin = 0;
     a.seg_end = h->S;
+    a.n_super = 0; a.sup_first = 0; a.sup_tile = nullptr; a.sup_basis = nullptr;
+    a.rest_lo0 = a.rest_lo1 = a.rest_hi0 = a.rest_hi1 = 0;
+    a.rest_list = nullptr; a.n_rest = 0; a.rest_run = 1;
+    a.pace = 0;
     return a;
+}
+
+// Splits the 16-slice tiles that touch the requested slice range into super-tiles of G tiles for the
+// fast phase (whole slices of one basis, wholly inside the gradient and the range) and rest tiles.
+// `which`: the handle's precomputed split for many bases (0: G = 128/d, 1: the bf16-pipe compress), used when the
+// whole gradient is requested; a partial range over many bases goes through the general phase.
+static void plan_tiles(const gvq_basis* h, CodecArgs& a, int G, bool fast_ok, int which)
+{
+    const int64_t T0 = a.seg_begin / TILE_SLICES, T1 = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES;
+    a.rest_lo0 = T0; a.rest_lo1 = T1; a.rest_hi0 = T1; a.rest_hi1 = T1;
+    if (!fast_ok) return;
+    if (h->B == 1) {
+        const int64_t full = h->M / h->d;   // slices that lie wholly inside the gradient
+        const int64_t p0 = (a.seg_begin + TILE_SLICES - 1) / TILE_SLICES;
+        const int64_t p1 = (a.seg_end < full ? a.seg_end : full) / TILE_SLICES;
+        if (p1 - p0 < G) return;
+        a.n_super = (p1 - p0) / G;
+        a.sup_first = p0;
+        a.rest_lo1 = p0;
+        a.rest_hi0 = p0 + a.n_super * G;
+        return;
+    }
+    const gvq_plan& pl = h->plan[which];
+    if (a.seg_begin != 0 || a.seg_end != h->S || !pl.d_rest) return;
+    a.n_super = pl.n_super; a.sup_tile = pl.d_sup_tile; a.sup_basis = pl.d_sup_basis;
+    a.rest_list = pl.d_rest; a.n_rest = pl.n_rest;
+}
+
+// Number of 128-bit words per lane that the compressed side of a super-tile needs, as the shift YS of
+// the kernels' template (words = max(1, (G * NT) >> YS), the smallest that covers ceil(G 16 k / 4 / 64)).
+static int pick_ys(int G, int NT, int k)
+{
+    const int need = (G * TILE_SLICES * (k >> 2) + 63) / 64;
+    int ys = 0;
+    while (ys < 2 && ((G * NT) >> (ys + 1)) >= need && ((G * NT) >> (ys + 1)) >= 1) ++ys;
+    return ys;
+}
+
+int gvq_build_plans(gvq_basis* h)
+{
+    if (h->B == 1 || !gvq_mfma_shape(h->d, h->k)) return GVQ_OK;
+    const int64_t T = (h->S + TILE_SLICES - 1) / TILE_SLICES, full = h->M / h->d;
+    for (int which = 0; which < 2; ++which) {
+        if (which == 1 && !gvq_bf16_pipe_shape(h)) break;
+        const int G = which ? (h->d == 128 ? 2 : 4) : 128 / h->d;   // bf16_super_tiles<D>() for which = 1
+        gvq_plan& pl = h->plan[which];
+        int64_t ns = 0;
+        for (int b = 0; b < h->B; ++b) {
+            const int64_t hi = h->h_offs[b + 1] < full ? h->h_offs[b + 1] : full;
+            const int64_t p0 = (h->h_offs[b] + TILE_SLICES - 1) / TILE_SLICES, p1 = hi / TILE_SLICES;
+            if (p1 - p0 >= G) ns += (p1 - p0) / G;
+        }
+        int64_t* st = (int64_t*)malloc(sizeof(int64_t) * (size_t)(ns ? ns : 1));
+        int* sb = (int*)malloc(sizeof(int) * (size_t)(ns ? ns : 1));
+        int64_t* rest = (int64_t*)malloc(sizeof(int64_t) * (size_t)T);
+        if (!st || !sb || !rest) { free(st); free(sb); free(rest); return GVQ_ENOMEM; }
+        int64_t i = 0, nr = 0, next = 0;   // next: first tile not yet assigned
+        for (int b = 0; b < h->B; ++b) {
+            const int64_t hi = h->h_offs[b + 1] < full ? h->h_offs[b + 1] : full;
+            const int64_t p0 = (h->h_offs[b] + TILE_SLICES - 1) / TILE_SLICES, p1 = hi / TILE_SLICES;
+            if (p1 - p0 < G) continue;
+            const int64_t n = (p1 - p0) / G;
+            while (next < p0) rest[nr++] = next++;
+            for (int64_t j = 0; j < n; ++j) { st[i] = p0 + j * G; sb[i] = b; ++i; }
+            next = p0 + n * G;
+        }
+        while (next < T) rest[nr++] = next++;
+        pl.n_super = ns; pl.n_rest = nr;
+        hipError_t e = hipMalloc((void**)&pl.d_sup_tile, sizeof(int64_t) * (size_t)(ns ? ns : 1));
+        if (e == hipSuccess) e = hipMalloc((void**)&pl.d_sup_basis, sizeof(int) * (size_t)(ns ? ns : 1));
+        if (e == hipSuccess) e = hipMalloc((void**)&pl.d_rest, sizeof(int64_t) * (size_t)(nr ? nr : 1));
+        if (e == hipSuccess && ns) e = hipMemcpy(pl.d_sup_tile, st, sizeof(int64_t) * (size_t)ns, hipMemcpyHostToDevice);
+        if (e == hipSuccess && ns) e = hipMemcpy(pl.d_sup_basis, sb, sizeof(int) * (size_t)ns, hipMemcpyHostToDevice);
+        if (e == hipSuccess && nr) e = hipMemcpy(pl.d_rest, rest, sizeof(int64_t) * (size_t)nr, hipMemcpyHostToDevice);
+        free(st); free(sb); free(rest);
+        if (e != hipSuccess) return gvq_hip_fail(e, "tile plan upload");
+    }
+    return GVQ_OK;
 }
 
 // `most`: upper limit on the work-groups per compute unit when the tuning option is not set
@@ -845,38 +1396,74 @@ static int streaming_grid(const gvq_basis* h, int64_t tiles, int most = 0)
 
 // Tiles per run for the MFMA kernels (see TileIter): the tuning option if set, else single
 // tiles for one basis and short runs when there are many bases.
-static int run_length(const gvq_basis* h, int64_t tiles, int grid)
+static int run_length(const gvq_basis* h, int64_t tiles, int grid, int many = 4)
 {
     const int64_t waves = (int64_t)grid * WAVES_PER_WG;
     const int64_t chunk = (tiles + waves - 1) / waves;   // run length that gives one run per wave
     int64_t r = gvq_opt_run_tiles();
-    if (r <= 0) r = h->B > 1 ? 4 : 1;
+    if (r <= 0) r = h->B > 1 ? many : 1;
     if (r > chunk) r = chunk;
     return (int)(r < 1 ? 1 : r);
 }
 
-template <int D, int NT, bool BF16, int VAR>
-static int launch_compress_v(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+// Launch shape of the fast phase.  This memory system gives its best with as few requests in flight
+// as keep it busy (measured on whole aggregation steps, GB/s of one kernel: d = 128 compress 5.95 with
+// two work-groups per compute unit and full pacing against 5.5 unpaced; d = 64 compress 6.1 with one
+// work-group and paced products against 5.6 with two; decompress 5.55 with one work-group against 5.2
+// with two), so every kernel has its own default.
+struct FastShape {
+    int wg_per_cu;   // most work-groups per compute unit
+    int pace;        // CodecArgs::pace
+    int many_run;    // super-tiles per run when there are many bases (each run reloads its basis)
+};
+static int pace_of(const FastShape& f) { return gvq_opt_pace() >= 0 ? gvq_opt_pace() : f.pace; }
+
+// Work items of a launch: super-tiles plus rest tiles; at least one per wave.
+static int64_t work_items(const CodecArgs& a)
 {
-    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false>;
-    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    // d = 64: two work-groups per compute unit stream 7 % faster than the four that fit (measured;
-    // d = 128 only fits two, d = 32 wants all it can get)
-    int grid = streaming_grid<kern>(h, tiles, D == 64 ? 2 : 0);
+    const int64_t rest = a.rest_list ? a.n_rest : (a.rest_lo1 - a.rest_lo0) + (a.rest_hi1 - a.rest_hi0);
+    return a.n_super + rest;
+}
+
+template <int D, int NT, bool BF16, int VAR, int YS>
+static int launch_compress_y(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+{
+    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, VAR, false, YS>;
+    const int64_t items = work_items(a);
+    constexpr FastShape fs = D == 128 ? FastShape{2, 5, 4} : D == 64 ? FastShape{1, 4, 4} : FastShape{1, 0, 4};
+    int grid = streaming_grid<kern>(h, items, fs.wg_per_cu);
     CodecArgs b = a;
-    b.run_tiles = run_length(h, tiles, grid);
+    b.pace = pace_of(fs);
+    b.run_tiles = run_length(h, a.n_super, grid, fs.many_run);
+    b.rest_run = run_length(h, work_items(a) - a.n_super, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
 
+template <int D, int NT, bool BF16, int VAR>
+static int launch_compress_v(const gvq_basis* h, const CodecArgs& a0, hipStream_t st)
+{
+    constexpr int G = 128 / D;
+    CodecArgs a = a0;
+    plan_tiles(h, a, G, (h->k & 3) == 0 && !(gvq_opt_no_fast() & 1), 0);
+    if constexpr (NT == 1 && D < 128) {
+        const int ys = pick_ys(G, NT, h->k);
+        if (ys == 1) return launch_compress_y<D, NT, BF16, VAR, 1>(h, a, st);
+        if constexpr (D < 64) {
+            if (ys == 2) return launch_compress_y<D, NT, BF16, VAR, 2>(h, a, st);
+        }
+    }
+    return launch_compress_y<D, NT, BF16, VAR, 0>(h, a, st);
+}
+
 template <int D, int NT, bool BF16>
 static int launch_compress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    // VAR bit 0: results leave through LDS as full-width stores (pays at k > 16, where a slice's
-    // results would otherwise leave in two half-line pieces); bit 1: raised wave priority
-    // while a wave feeds the MFMA pipe.  Both measured: +1..3 %.  Bit 2: fused ring step
-    // (adds acc_in); a separate instantiation so that the plain kernel does not carry its registers.
+    // VAR bit 0 (general phase): results leave through LDS as full-width stores (pays at k > 16, where a
+    // slice's results would otherwise leave in two half-line pieces); bit 1: raised wave priority
+    // while a wave feeds the MFMA pipe.  Bit 2: fused ring step (adds acc_in); a separate
+    // instantiation so that the plain kernel does not carry its registers.
     if (a.acc_in) return launch_compress_v<D, NT, BF16, (NT == 2 ? 7 : 6)>(h, a, st);
     return launch_compress_v<D, NT, BF16, (NT == 2 ? 3 : 2)>(h, a, st);
 }
@@ -884,20 +1471,39 @@ static int launch_compress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t
 template <int D, bool BF16>
 static int launch_compress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    return h->k <= 16 ? launch_compress_t<D, 1, BF16>(h, a, st) : launch_compress_t<D, 2, BF16>(h, a, st);
+    if constexpr (D == 16) return launch_compress_t<D, 1, BF16>(h, a, st);   // k <= d = 16
+    else return h->k <= 16 ? launch_compress_t<D, 1, BF16>(h, a, st) : launch_compress_t<D, 2, BF16>(h, a, st);
 }
 
-template <int D, int NT, bool ACC>
-static int launch_compress_bf16_a(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+template <int D, int NT, bool ACC, int YS>
+static int launch_compress_bf16_y(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    constexpr auto kern = compress_bf16_kernel<D, NT, ACC>;
-    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid<kern>(h, tiles);
+    constexpr auto kern = compress_bf16_kernel<D, NT, ACC, YS>;
+    constexpr FastShape fs = {1, 0, 4};
+    int grid = streaming_grid<kern>(h, work_items(a), fs.wg_per_cu);
     CodecArgs b = a;
-    b.run_tiles = run_length(h, tiles, grid);
+    b.pace = pace_of(fs);
+    b.run_tiles = run_length(h, a.n_super, grid, fs.many_run);
+    b.rest_run = run_length(h, work_items(a) - a.n_super, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
+}
+
+template <int D, int NT, bool ACC>
+static int launch_compress_bf16_a(const gvq_basis* h, const CodecArgs& a0, hipStream_t st)
+{
+    constexpr int G = bf16_super_tiles<D>();
+    CodecArgs a = a0;
+    plan_tiles(h, a, G, (h->k & 3) == 0 && !(gvq_opt_no_fast() & 2), 1);
+    if constexpr (NT == 1) {
+        const int ys = pick_ys(G, NT, h->k);
+        if (ys == 1) return launch_compress_bf16_y<D, NT, ACC, 1>(h, a, st);
+        if constexpr (G == 4) {
+            if (ys == 2) return launch_compress_bf16_y<D, NT, ACC, 2>(h, a, st);
+        }
+    }
+    return launch_compress_bf16_y<D, NT, ACC, 0>(h, a, st);
 }
 
 template <int D, int NT>
@@ -932,10 +1538,11 @@ int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int
     const bool bf = h->dtype == GVQ_BF16;
     if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
+        // bf16-stored gradients reach this point with d = 16 only (longer slices took the bf16 pipe above)
         case 16: return bf ? launch_compress_d<16, true>(h, a, st) : launch_compress_d<16, false>(h, a, st);
-        case 32: return bf ? launch_compress_d<32, true>(h, a, st) : launch_compress_d<32, false>(h, a, st);
-        case 64: return bf ? launch_compress_d<64, true>(h, a, st) : launch_compress_d<64, false>(h, a, st);
-        case 128: return bf ? launch_compress_d<128, true>(h, a, st) : launch_compress_d<128, false>(h, a, st);
+        case 32: return launch_compress_d<32, false>(h, a, st);
+        case 64: return launch_compress_d<64, false>(h, a, st);
+        case 128: return launch_compress_d<128, false>(h, a, st);
         default: break;
         }
     }
@@ -950,23 +1557,44 @@ int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int
     return GVQ_OK;
 }
 
-template <int D, int NQ, bool OBF>
-static int launch_decompress_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
+template <int D, int NQ, bool OBF, int YS>
+static int launch_decompress_y(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    constexpr auto kern = decompress_mfma_kernel<D, NQ, OBF>;
-    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid<kern>(h, tiles);
+    constexpr auto kern = decompress_mfma_kernel<D, NQ, OBF, YS>;
+    const int64_t items = work_items(a);
+    // many bases: the basis reload of every run has to be hidden by a second work-group
+    const FastShape fs = h->B > 1 ? FastShape{2, 0, 8} : FastShape{1, 0, 1};
+    int grid = streaming_grid<kern>(h, items, fs.wg_per_cu);
     CodecArgs b = a;
-    b.run_tiles = run_length(h, tiles, grid);
+    b.pace = pace_of(fs);
+    b.run_tiles = run_length(h, a.n_super, grid, fs.many_run);
+    b.rest_run = run_length(h, work_items(a) - a.n_super, grid);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
 
+template <int D, int NQ, bool OBF>
+static int launch_decompress_t(const gvq_basis* h, const CodecArgs& a0, hipStream_t st)
+{
+    constexpr int G = 128 / D;
+    CodecArgs a = a0;
+    plan_tiles(h, a, G, (h->k & 3) == 0 && !(gvq_opt_no_fast() & 4), 0);
+    if constexpr (NQ == 1 && D < 128) {
+        const int ys = pick_ys(G, NQ, h->k);
+        if (ys == 1) return launch_decompress_y<D, NQ, OBF, 1>(h, a, st);
+        if constexpr (D < 64) {
+            if (ys == 2) return launch_decompress_y<D, NQ, OBF, 2>(h, a, st);
+        }
+    }
+    return launch_decompress_y<D, NQ, OBF, 0>(h, a, st);
+}
+
 template <int D, bool OBF>
 static int launch_decompress_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    return h->k <= 16 ? launch_decompress_t<D, 1, OBF>(h, a, st) : launch_decompress_t<D, 2, OBF>(h, a, st);
+    if constexpr (D == 16) return launch_decompress_t<D, 1, OBF>(h, a, st);   // k <= d = 16
+    else return h->k <= 16 ? launch_decompress_t<D, 1, OBF>(h, a, st) : launch_decompress_t<D, 2, OBF>(h, a, st);
 }
 
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
@@ -1101,11 +1729,11 @@ __global__ __launch_bounds__(256) void loss_reduce2_kernel(const double* part, i
 template <int D, int NT, bool BF16>
 static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, 0, true>;
-    int64_t tiles = (a.seg_end + TILE_SLICES - 1) / TILE_SLICES - a.seg_begin / TILE_SLICES;
-    int grid = streaming_grid<kern>(h, tiles);
+    constexpr auto kern = compress_mfma_kernel<D, NT, BF16, 0, true, 0>;
     CodecArgs b = a;
-    b.run_tiles = run_length(h, tiles, grid);
+    plan_tiles(h, b, 128 / D, false, 0);   // the residual kernel has no fast phase: every tile is a rest tile
+    int grid = streaming_grid<kern>(h, work_items(b));
+    b.run_tiles = 1;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
@@ -1114,17 +1742,20 @@ static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 template <int D, bool BF16>
 static int launch_loss_d(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
-    return h->k <= 16 ? launch_loss_t<D, 1, BF16>(h, a, st) : launch_loss_t<D, 2, BF16>(h, a, st);
+    if constexpr (D == 16) return launch_loss_t<D, 1, BF16>(h, a, st);
+    else return h->k <= 16 ? launch_loss_t<D, 1, BF16>(h, a, st) : launch_loss_t<D, 2, BF16>(h, a, st);
 }
 
-int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out, hipStream_t st)
+// loss_slice [S] and loss_part [B][loss_groups]: the scratch of the two reduction stages.
+static int launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out, hipStream_t st,
+                             float* loss_slice, double* loss_part)
 {
-    CodecArgs a = make_args(h, grad, h->d_loss_slice, n_workers, h->d_Upc);
+    CodecArgs a = make_args(h, grad, loss_slice, n_workers, h->d_Upc);
     a.Upack2 = (const f4*)h->d_Upd;
     const bool bf = h->dtype == GVQ_BF16;
     int rc = GVQ_OK;
     if (gvq_long_shape(h->d, h->k)) {
-        rc = gvq_launch_loss_long(h, grad, n_workers, h->d_loss_slice, st);
+        rc = gvq_launch_loss_long(h, grad, n_workers, loss_slice, st);
     } else if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {
         case 16: rc = bf ? launch_loss_d<16, true>(h, a, st) : launch_loss_d<16, false>(h, a, st); break;
@@ -1143,10 +1774,14 @@ int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, d
     }
     if (rc != GVQ_OK) return rc;
     const int G = h->loss_groups;
-    hipLaunchKernelGGL(loss_reduce1_kernel, dim3(G, h->B), dim3(256), 0, st, h->d_loss_slice, h->d_offs, G,
-                       h->d_loss_part);
+    hipLaunchKernelGGL(loss_reduce1_kernel, dim3(G, h->B), dim3(256), 0, st, loss_slice, h->d_offs, G, loss_part);
     GVQ_HIP(hipGetLastError());
-    hipLaunchKernelGGL(loss_reduce2_kernel, dim3(h->B), dim3(256), 0, st, h->d_loss_part, G, loss_out);
+    hipLaunchKernelGGL(loss_reduce2_kernel, dim3(h->B), dim3(256), 0, st, loss_part, G, loss_out);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
+}
+
+int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out, hipStream_t st)
+{
+    return launch_local_loss(h, grad, n_workers, loss_out, st, h->d_loss_slice, h->d_loss_part);
 }

@@ -1,6 +1,7 @@
 // Device-side helpers shared by the codec and monitor kernels (gfx950).
 #pragma once
 #include "gvq_internal.h"
+#include <type_traits>
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
@@ -29,6 +30,21 @@ struct CodecArgs {
     float n_workers;      // compress only
     const int* tile_block;  // [T] basis of the first slice of every 16-slice tile (B > 1 only)
     int run_tiles;        // tile schedule, see TileIter
+    // Fast phase of the register-resident kernels: "super-tiles" of whole slices of ONE basis that lie
+    // wholly inside the gradient and the requested range (2048 gradient elements each, i.e. 128/d
+    // consecutive 16-slice tiles for fp32 input; 256/d for the bf16-pipe compress).  Everything else is a
+    // "rest" tile and goes through the bounds-checked general phase.
+    int64_t n_super;          // super-tiles (0 = no fast phase)
+    int64_t sup_first;        // sup_tile == null: super-tile p starts at 16-slice tile sup_first + p * G
+    const int64_t* sup_tile;  // many bases: [n_super] first 16-slice tile of every super-tile
+    const int* sup_basis;     // many bases: [n_super] its basis
+    int64_t rest_lo0, rest_lo1, rest_hi0, rest_hi1;   // rest_list == null: the rest tiles are [lo0, lo1) and [hi0, hi1)
+    const int64_t* rest_list; // many bases: [n_rest] the rest tiles
+    int64_t n_rest;
+    int rest_run;             // rest tiles per run, see RestIter
+    int pace;                 // fast phase: bit 0 = wait for all memory work before a super-tile is parked,
+                              // bit 1 = also after its matrix products (fewer requests in flight per wave), bit 2 = the matrix
+                              // products of a super-tile wait for the next one's loads one by one
 };
 
 // Largest b with offs[b] <= j (offs[0] = 0, offs[B] = S > j).
@@ -122,10 +138,109 @@ struct TileIter {
     }
 };
 
-// The 16-slice tiles that touch the requested slice range.
-__device__ __forceinline__ bool init_tiles(TileIter& it, const CodecArgs& a)
+// This wave's index in the grid and the number of waves, as scalars (wave-uniform values the
+// compiler would otherwise keep in vector registers because they derive from threadIdx).
+__device__ __forceinline__ int64_t grid_wave()
 {
-    return it.init(a.seg_begin / TILE_SLICES, (a.seg_end + TILE_SLICES - 1) / TILE_SLICES, a.run_tiles);
+    return (int64_t)blockIdx.x * WAVES_PER_WG + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+}
+__device__ __forceinline__ int64_t grid_waves() { return (int64_t)gridDim.x * WAVES_PER_WG; }
+
+// The super-tiles of one wave in the fast phase: runs of R consecutive ones, runs interleaved
+// across the grid (see TileIter), all scalar.
+struct SuperIter {
+    int64_t p, run, run_end, N, W;
+    int R;
+    __device__ __forceinline__ bool init(int64_t N_, int R_)
+    {
+        N = N_; R = R_;
+        W = grid_waves();
+        run = grid_wave();
+        p = run * R;
+        run_end = p + R < N ? p + R : N;
+        return p < N;
+    }
+    __device__ __forceinline__ bool advance()
+    {
+        if (++p < run_end) return true;
+        run += W;
+        p = run * R;
+        run_end = p + R < N ? p + R : N;
+        return p < N;
+    }
+};
+
+// The rest tiles of one wave (general phase): runs of R consecutive items, runs interleaved across the
+// grid, counted from the far end so that the waves with the fewest super-tiles take them first.
+struct RestIter {
+    int64_t t, i, run, run_end, n, W, lo0, nlo, hi0;
+    int R;
+    const int64_t* list;
+    __device__ __forceinline__ int64_t tile_of(int64_t j) const
+    {
+        if (list) return list[j];
+        return j < nlo ? lo0 + j : hi0 + (j - nlo);
+    }
+    __device__ __forceinline__ bool init(const CodecArgs& a)
+    {
+        list = a.rest_list;
+        lo0 = a.rest_lo0; nlo = a.rest_lo1 - a.rest_lo0; hi0 = a.rest_hi0;
+        n = list ? a.n_rest : nlo + (a.rest_hi1 - a.rest_hi0);
+        R = a.rest_run;
+        W = grid_waves();
+        run = W - 1 - grid_wave();
+        i = run * R;
+        run_end = i + R < n ? i + R : n;
+        if (i >= n) return false;
+        t = tile_of(i);
+        return true;
+    }
+    __device__ __forceinline__ bool advance()
+    {
+        if (++i >= run_end) {
+            run += W;
+            i = run * R;
+            run_end = i + R < n ? i + R : n;
+            if (i >= n) return false;
+        }
+        t = tile_of(i);
+        return true;
+    }
+};
+
+// Load through the scalar cache: the address must be the same for the whole wave and the memory must
+// not change while the kernel runs (tables the host wrote before the launch).  Scalar loads count on
+// their own counter, so they do not disturb the bookkeeping of the vector loads and stores around them.
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T* p)
+{
+    typedef const T __attribute__((address_space(4))) CT;
+    return *(CT*)(uintptr_t)p;
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// At most N of this wave's vector-memory requests are still outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void wait_vmem_at_most()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));   // expcnt, lgkmcnt untouched
+}
+
+// Everything this wave asked of memory has arrived (loads) or been accepted (stores); also tells the
+// compiler's wait-count bookkeeping so, which keeps a loop that follows free of inherited waits.
+__device__ __forceinline__ void drain_memory()
+{
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0), expcnt untouched
 }
 
 // Ring step of Algorithm 1: the partial sum that arrived from the predecessor, in the register

@@ -49,6 +49,7 @@ struct MomMfmaArgs {
     int wgs;         // work-groups per basis (each holds 4 sample streams, 2 at d = 128)
     int accumulate;  // 0: overwrite the partials, 1: add to them
     double* part;    // [B][wgs * streams][packed width]
+    unsigned long long* nsamp;   // [B] += the sample slices this launch took in
 };
 
 // HALF selects which tile pairs this wave accumulates: with SPLIT = 2 (d = 128) the 36 pairs
@@ -80,9 +81,11 @@ __device__ __forceinline__ void moments_mfma_body(const MomMfmaArgs& a, int stre
     for (int i = 0; i < NTL; ++i) sacc[i] = 0.0;
 
     // raw loads of one group of 4 samples: this lane's sample is j = first + kk
+    unsigned int taken = 0;   // samples this lane's group slot held (lanes with m = 0 of the counting waves)
     auto load_group = [&](const void* g, int64_t first, float (&x)[NTL]) {
         const int64_t j = first + kk;
         const bool ok = j < j1;
+        taken += ok ? 1u : 0u;
         if (D >= 64) {
 #pragma unroll
             for (int q = 0; q < NLD; ++q) {
@@ -159,6 +162,11 @@ __device__ __forceinline__ void moments_mfma_body(const MomMfmaArgs& a, int stre
             *o = a.accumulate ? *o + acc[pi - P0][r] : acc[pi - P0][r];
         }
     if (HALF == 0) {
+        // every group that was loaded inside the range was also multiplied: count its samples once
+        unsigned int cnt = m == 0 ? taken : 0u;
+        cnt += __shfl_xor(cnt, 16, 64);
+        cnt += __shfl_xor(cnt, 32, 64);
+        if (lane == 0 && cnt) atomicAdd(a.nsamp + b, (unsigned long long)cnt);
         // sums: add the four sample lanes kk of every element
 #pragma unroll
         for (int T = 0; T < NTL; ++T) {
@@ -238,10 +246,8 @@ __global__ void unpack_moments_kernel(const double* packed, double* mom, int D)
 // --------------------------------------------------------------------------------------
 struct EigArgs {
     const double* mom;     // [B][d*d+d]
-    const int64_t* offs;
-    int64_t M;
-    int L, d, k;
-    int first_slice_only;  // samples of a basis: its first slice only (one per gradient)
+    const unsigned long long* nsamp;   // [B] samples behind the moments
+    int d, k;
     double* cov;           // [B][d][d]
     double* V;             // [B][n][n]
     double* eig;           // [B][d]
@@ -281,8 +287,8 @@ __device__ __forceinline__ int jacobi_lds_sweeps(double* A, double* V, int n, do
             if (r != c) off2 += A[i] * A[i];
         }
         off2 = block_sum(off2, red);
+        if (off2 != off2 || fro2 != fro2) break;  // NaN: no convergence (sweeps_used stays -1)
         if (!(off2 > tol * tol * fro2)) { sweeps_used = sweep; break; }
-        if (off2 != off2) break;  // NaN: give up
         if (sweep == max_sweeps) break;
 
         for (int round = 0; round < n - 1; ++round) {
@@ -360,9 +366,7 @@ __global__ void eigen_kernel(EigArgs a)
 
     const int W = d * d + d;
     const double* mom = a.mom + (size_t)b * W;
-    const int64_t full = a.M / d;
-    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
-    const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
+    const double ns = (double)a.nsamp[b];
 
     double* V = a.V + (size_t)b * n * n;
     double* cov = a.cov + (size_t)b * d * d;
@@ -433,6 +437,7 @@ struct GramArgs {
     gvq_ptrs grads[GVQ_GRAM_MAX_L / GVQ_MAX_PTRS];
     int L;
     const double* mom;     // [B][d*d+d] from first_slice_moments_kernel
+    const unsigned long long* nsamp;   // [B] samples behind the moments (L, or 0 without a full first slice)
     const int64_t* offs;
     int64_t M;
     int d, k, bf16;
@@ -473,7 +478,7 @@ __global__ __launch_bounds__(1024) void gram_eigen_kernel(GramArgs a)
     double* V = a.work + (size_t)b * a.work_stride;   // [m][m]
     double* Uw = V + (size_t)m * m;                   // [k][d]
     const int64_t j = a.offs[b];
-    if ((j + 1) * d > a.M) {
+    if (a.nsamp[b] == 0) {
         // no full first slice: the trivial basis, as in the general solver
         for (int i = tid; i < d * d; i += nth) cov[i] = 0.0;
         for (int i = tid; i < d; i += nth) { a.mu[(size_t)b * d + i] = 0.f; a.eig[(size_t)b * d + i] = 0.0; }
@@ -481,7 +486,7 @@ __global__ __launch_bounds__(1024) void gram_eigen_kernel(GramArgs a)
         if (tid == 0) a.sweeps[b] = 0;
         return;
     }
-    const double ns = (double)L;
+    const double ns = (double)a.nsamp[b];   // = L
     for (int i = tid; i < d * d; i += nth) {
         const int r = i / d, c = i - r * d;
         cov[i] = mom[i] / ns - (mom[(size_t)d * d + r] / ns) * (mom[(size_t)d * d + c] / ns);
@@ -605,11 +610,12 @@ bool gvq_gram_shape(int d, int k, int L)
 // Section 3, "compressor reuse": moments of the first slice of every basis only -- L samples of d
 // numbers per basis, a few KB; one work-group per basis, one thread per matrix entry.
 __global__ void first_slice_moments_kernel(gvq_ptrs grads, int L, const int64_t* offs, int64_t M, int d, int bf16,
-                                           int accumulate, double* mom)
+                                           int accumulate, double* mom, unsigned long long* nsamp)
 {
     const int b = blockIdx.x, W = d * d + d;
     const int64_t j = offs[b];
     const bool ok = (j + 1) * d <= M;     // the first slice must be a full one
+    if (blockIdx.y == 0 && threadIdx.x == 0 && ok) atomicAdd(nsamp + b, (unsigned long long)L);
     for (int i = blockIdx.y * blockDim.x + threadIdx.x; i < W; i += gridDim.y * blockDim.x) {
         const int r = i < d * d ? i / d : i - d * d, c = i < d * d ? i % d : -1;
         double acc = 0.0;
@@ -674,9 +680,18 @@ bool gvq_moments_mfma_shape(int d) { return d == 16 || d == 32 || d == 64 || d =
 int gvq_moments_packed_width(int d) { return mom_packed_width(d); }
 int gvq_moments_streams(int d) { return d == 128 ? 2 : 4; }
 
+// A fill kernel rather than a memset, so that a fit can be captured into a HIP graph.
+__global__ void zero_counts_kernel(unsigned long long* p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_slice_only, hipStream_t st)
 {
     const int d = h->d, W = d * d + d;
+    hipLaunchKernelGGL(zero_counts_kernel, dim3((h->B + 255) / 256), dim3(256), 0, st, h->d_nsamp, h->B);
+    GVQ_HIP(hipGetLastError());
     if (first_slice_only) {
         for (int l0 = 0; l0 < L; l0 += GVQ_MAX_PTRS) {
             gvq_ptrs p;
@@ -684,7 +699,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
             for (int i = 0; i < n; ++i) p.p[i] = grads[l0 + i];
             hipLaunchKernelGGL(first_slice_moments_kernel, dim3(h->B, (W + 4095) / 4096), dim3(256), 0, st, p, n,
                                h->d_offs, h->M, d,
-                               h->dtype == GVQ_BF16 ? 1 : 0, l0 > 0 ? 1 : 0, h->d_mom);
+                               h->dtype == GVQ_BF16 ? 1 : 0, l0 > 0 ? 1 : 0, h->d_mom, h->d_nsamp);
             GVQ_HIP(hipGetLastError());
         }
     } else if (!gvq_moments_mfma_shape(d)) {
@@ -697,6 +712,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
             a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
             for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
             a.offs = h->d_offs; a.M = h->M; a.wgs = h->mom_wgs; a.accumulate = l0 > 0; a.part = h->d_part;
+            a.nsamp = h->d_nsamp;
             switch (d) {
             case 16: launch_moments_mfma<16>(h, a, st); break;
             case 32: launch_moments_mfma<32>(h, a, st); break;
@@ -721,7 +737,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
     if (first_slice_only && gvq_gram_shape(d, h->k, L)) {
         GramArgs g;
         for (int l = 0; l < L; ++l) g.grads[l / GVQ_MAX_PTRS].p[l % GVQ_MAX_PTRS] = grads[l];
-        g.L = L; g.mom = h->d_mom; g.offs = h->d_offs; g.M = h->M; g.d = d; g.k = h->k;
+        g.L = L; g.mom = h->d_mom; g.nsamp = h->d_nsamp; g.offs = h->d_offs; g.M = h->M; g.d = d; g.k = h->k;
         g.bf16 = h->dtype == GVQ_BF16 ? 1 : 0;
         g.cov = h->d_cov; g.work = h->d_V; g.work_stride = (size_t)(d + (d & 1)) * (d + (d & 1));
         g.eig = h->d_eig; g.U = h->d_U; g.mu = h->d_mu; g.sweeps = h->d_sweeps; g.max_sweeps = 60; g.tol = 1e-15;
@@ -740,8 +756,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         return rc != GVQ_OK ? rc : gvq_launch_pack(h, st);
     }
     EigArgs e;
-    e.mom = h->d_mom; e.offs = h->d_offs; e.M = h->M; e.L = L; e.d = d; e.k = h->k;
-    e.first_slice_only = first_slice_only ? 1 : 0;
+    e.mom = h->d_mom; e.nsamp = h->d_nsamp; e.d = d; e.k = h->k;
     e.cov = h->d_cov; e.V = h->d_V; e.eig = h->d_eig; e.U = h->d_U; e.mu = h->d_mu;
     e.sweeps = h->d_sweeps; e.max_sweeps = 60; e.tol = 1e-15;
     const size_t lds = gvq_eigen_lds_bytes(d);

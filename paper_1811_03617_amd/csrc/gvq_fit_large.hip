@@ -24,6 +24,7 @@ struct MomLargeArgs {
     int d, ng, npairs, chunks;
     int accumulate;
     double* part;   // [B][npairs][chunks][LBLOCK]
+    unsigned long long* nsamp;   // [B] += the sample slices this launch took in (counted by the waves of block pair 0)
 };
 
 __device__ __forceinline__ float large_elem(const void* g, bool bf16, int64_t idx)
@@ -94,6 +95,7 @@ __global__ __launch_bounds__(256, 2) void moments_large_kernel(MomLargeArgs a)
     // PF groups of 4 samples are in flight ahead of the one being multiplied (one group is 1024
     // matrix-pipe cycles, a load from HBM takes several times that)
     constexpr int PF = 4;
+    unsigned int taken = 0;   // samples multiplied by this lane's slot
     for (int l = 0; l < a.L; ++l) {
         const void* g = a.grads.p[l];
         float xa[PF][4], xb[PF][4];
@@ -105,6 +107,7 @@ __global__ __launch_bounds__(256, 2) void moments_large_kernel(MomLargeArgs a)
         for (int64_t j = j0; j < j1; j += 4 * PF) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
+                taken += (pair == 0 && m == 0 && j + 4 * u + kk < j1) ? 1u : 0u;
                 double da[4], db[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
@@ -124,6 +127,12 @@ __global__ __launch_bounds__(256, 2) void moments_large_kernel(MomLargeArgs a)
         }
     }
 
+    if (pair == 0) {
+        unsigned int cnt = taken;
+        cnt += __shfl_xor(cnt, 16, 64);
+        cnt += __shfl_xor(cnt, 32, 64);
+        if (lane == 0 && cnt) atomicAdd(a.nsamp + b, (unsigned long long)cnt);
+    }
     double* out = a.part + (((size_t)b * a.npairs + pair) * a.chunks + chunk) * LBLOCK;
 #pragma unroll
     for (int c1 = 0; c1 < 4; ++c1)
@@ -190,7 +199,7 @@ int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipS
         a.L = L - l0 < GVQ_MAX_PTRS ? L - l0 : GVQ_MAX_PTRS;
         for (int i = 0; i < a.L; ++i) a.grads.p[i] = grads[l0 + i];
         a.offs = h->d_offs; a.M = h->M; a.d = d; a.ng = ng; a.npairs = npairs; a.chunks = h->P;
-        a.accumulate = l0 > 0; a.part = h->d_part;
+        a.accumulate = l0 > 0; a.part = h->d_part; a.nsamp = h->d_nsamp;
         const int64_t tasks = (int64_t)npairs * h->P;
         dim3 grid((unsigned)((tasks + 3) / 4), h->B);
         const bool bf = h->dtype == GVQ_BF16, vec = (d & 3) == 0;
@@ -212,10 +221,8 @@ int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipS
 // ======================================================================================
 struct JacArgs {
     const double* mom;     // [B][d*d+d]
-    const int64_t* offs;
-    int64_t M;
-    int L, d, n, k;
-    int first_slice_only;
+    const unsigned long long* nsamp;   // [B] samples behind the moments
+    int d, n, k;
     double* cov;           // [B][d][d]
     double* jac;           // [B][2][n][n]
     double* V;             // [B][n][n]
@@ -233,9 +240,7 @@ __global__ __launch_bounds__(256) void jacobi_init_kernel(JacArgs a)
 {
     const int b = blockIdx.y, d = a.d, n = a.n;
     const double* mom = a.mom + (size_t)b * ((size_t)d * d + d);
-    const int64_t full = a.M / d;
-    const int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
-    const double ns = hi > lo ? (double)((a.first_slice_only ? 1 : hi - lo) * (int64_t)a.L) : 0.0;
+    const double ns = (double)a.nsamp[b];
     double* A = a.jac + (size_t)b * 2 * n * n;
     double* V = a.V + (size_t)b * n * n;
     double* cov = a.cov + (size_t)b * d * d;
@@ -411,8 +416,8 @@ int gvq_launch_eigen_large(gvq_basis* h, int L, bool first_slice_only, hipStream
 {
     const int d = h->d, n = d + (d & 1), half = n / 2;
     JacArgs a;
-    a.mom = h->d_mom; a.offs = h->d_offs; a.M = h->M; a.L = L; a.d = d; a.n = n; a.k = h->k;
-    a.first_slice_only = first_slice_only ? 1 : 0;
+    a.mom = h->d_mom; a.nsamp = h->d_nsamp; a.d = d; a.n = n; a.k = h->k;
+    (void)L; (void)first_slice_only;
     a.cov = h->d_cov; a.jac = h->d_jac; a.V = h->d_V; a.eig = h->d_eig; a.U = h->d_U; a.mu = h->d_mu;
     a.sweeps = h->d_sweeps; a.state = h->d_jstate; a.tol = 1e-15;
     const int max_sweeps = 24;

@@ -8,6 +8,16 @@
 #define GVQ_MAX_PTRS 32  // device pointers passed by value in one kernel launch
 #define GVQ_LDS_EIGEN_MAX_D 128  // longest slice whose d x d matrix the one-work-group eigensolver holds in LDS
 
+// Many bases: the split of the gradient's 16-slice tiles into super-tiles (G consecutive tiles of
+// whole slices of one basis, for the branch-free fast phase of the register-resident codec kernels)
+// and the rest, made once per handle.
+struct gvq_plan {
+    int64_t n_super = 0, n_rest = 0;
+    int64_t* d_sup_tile = nullptr;   // [n_super] first 16-slice tile
+    int* d_sup_basis = nullptr;      // [n_super] basis
+    int64_t* d_rest = nullptr;       // [n_rest] the tiles no super-tile covers
+};
+
 struct gvq_basis {
     int64_t M = 0, S = 0;       // elements, slices
     int d = 0, k = 0, B = 0;    // slice length, kept components, number of bases
@@ -17,6 +27,7 @@ struct gvq_basis {
     int64_t* h_offs = nullptr;  // host [B+1]
     int64_t* d_offs = nullptr;  // device [B+1]
     int* d_tile_block = nullptr;  // device [ceil(S/16)]: basis of the first slice of each 16-slice tile (B > 1)
+    gvq_plan plan[2];             // B > 1, register-resident shapes: G = 128/d, and the bf16-pipe compress's G
     int64_t* h_ltile = nullptr; // host [B+1]: first 128-slice tile of each basis (long slices, B > 1)
     int64_t* d_ltile = nullptr; // device copy
     float* d_U = nullptr;       // [B][d][k]
@@ -35,6 +46,7 @@ struct gvq_basis {
     double* d_part2 = nullptr;  // [B][ceil(P/32)][width] second level of the partial sum (MFMA path)
     int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
+    unsigned long long* d_nsamp = nullptr;  // [B] sample slices the moment kernels of the last fit took in, counted by them
     double* d_jac = nullptr;    // [B][2][dp][dp] matrix buffers of the global-memory Jacobi (d > 128 only)
     int* d_jstate = nullptr;    // [B][4] its per-basis state (d > 128 only)
     int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
@@ -68,6 +80,11 @@ int gvq_opt_wg_per_cu();
 int gvq_opt_run_tiles();
 // LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split.
 int gvq_opt_long_mode();
+// Bit mask: send every tile through the bounds-checked general phase (1: fp32-pipe compress, 2: bf16-pipe
+// compress, 4: decompress).
+int gvq_opt_no_fast();
+// Pacing of the fast phase (CodecArgs::pace), -1 = each kernel's default.
+int gvq_opt_pace();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
@@ -85,6 +102,7 @@ int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st);
 // Refresh the operand-order copies of U after d_U changed (no-op for non-MFMA shapes).
 int gvq_launch_pack(const gvq_basis* h, hipStream_t st);
 bool gvq_mfma_shape(int d, int k);
+int gvq_build_plans(gvq_basis* h);   // fills h->plan (needs h_offs; no-op for one basis or other shapes)
 bool gvq_bf16_pipe_shape(const gvq_basis* h);
 bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);

@@ -35,6 +35,10 @@ def lib():
         import torch  # noqa: F401
         if not os.path.exists(_build.LIB):
             _build.build()
+        elif _build.needs_build():
+            import warnings
+            warnings.warn("libgvq.so is older than its sources (csrc/ or include/gvq.h): run "
+                          "`python -m paper_1811_03617_amd.build` before trusting tests or timings", RuntimeWarning)
         L = C.CDLL(_build.LIB)
         vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
         L.gvq_basis_create.argtypes = [C.POINTER(vp), i64, i32, i32, i32, C.POINTER(i64), i32]

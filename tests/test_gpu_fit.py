@@ -114,8 +114,10 @@ def test_block_without_full_slice_gets_the_trivial_basis():
     b.close()
 
 
-def test_fit_reports_non_finite_input():
-    M, d, k = 16 * 200, 16, 4
+@pytest.mark.parametrize("d", [16, 192])   # the eigensolver in LDS, and the one out of global memory
+def test_fit_reports_non_finite_input(d):
+    import ctypes as C
+    M, k = d * 200, 4
     g = torch.randn(M, generator=torch.Generator().manual_seed(4))
     g[37] = float("nan")
     b = gvq.Basis(M, d, k)
@@ -123,6 +125,10 @@ def test_fit_reports_non_finite_input():
     with pytest.raises(gvq.GvqError) as ei:
         b.fit_status()
     assert ei.value.status == gvq.ENONFINITE
+    # both routes record "no convergence" for the basis, so no sweep count is reported for it
+    sw = C.c_int(-5)
+    rc = gvq.lib().gvq_fit_status(b.handle, C.byref(sw), torch.cuda.current_stream().cuda_stream)
+    assert rc == gvq.ENONFINITE and sw.value == 0
     b.close()
 
 

@@ -78,6 +78,13 @@ def test_moments_equal_numpy_mean_and_cov(d, M):
     np.testing.assert_allclose(C, np.cov(X.T, bias=True), rtol=0, atol=1e-13)
     a, b = 1, d - 1
     assert abs(oracle.cov_entry(grads, d, a, b) - C[a, b]) < 1e-13
+    # the mean on its own (used where the whole covariance is too slow) is the same numpy mean,
+    # also on a sub-range of the slices
+    np.testing.assert_allclose(oracle.mean(grads, d), X.mean(axis=0), rtol=0, atol=1e-14)
+    s0, s1 = 1, full - 1
+    if s1 > s0:
+        Xs = np.concatenate([g[s0 * d: s1 * d].reshape(s1 - s0, d) for g in grads]).astype(np.float64)
+        np.testing.assert_allclose(oracle.mean(grads, d, s0=s0, s1=s1), Xs.mean(axis=0), rtol=0, atol=1e-14)
 
 
 @pytest.mark.parametrize("n", [2, 3, 8, 16, 47, 128])
