@@ -55,10 +55,12 @@ typedef enum {
     GVQ_EHIP = -4,       /* a HIP call failed; gvq_strerror gives the HIP text */
     GVQ_ENOMEM = -5,     /* host or device allocation failed */
     GVQ_ENONFINITE = -6, /* gvq_fit_status: a fitted eigenvalue is NaN or Inf */
-    GVQ_ENOCONV = -7     /* gvq_fit_status: the eigensolver hit its sweep limit */
+    GVQ_ENOCONV = -7,    /* gvq_fit_status: the eigensolver hit its sweep limit */
+    GVQ_ETOOBIG = -8     /* gvq_local_loss_static: more slices or bases than its fixed scratch buffer holds */
 } gvq_status_t;
 
 #define GVQ_MAX_D 1024      /* largest supported slice length */
+#define GVQ_STATIC_MAX_SLICES 2097152 /* most slices gvq_local_loss_static takes (2^21) */
 #define GVQ_MAX_BASES 65535 /* most bases per handle (the basis index is a grid dimension of the fit kernels) */
 
 /*
@@ -182,6 +184,22 @@ int gvq_decompress_segment(const gvq_basis_t* h, const float* comp_sum, int64_t 
  */
 int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out,
                    void* stream);
+
+/*
+ * gvq_local_loss for callers that cannot allocate device memory and cannot let a library do it for
+ * them: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and same result as gvq_local_loss, but the scratch of the two reduction
+ * stages (one float per slice, then a few partial sums per basis) lives in a fixed buffer inside the
+ * library, about 8.5 MB per GPU, held until the process ends, instead of in the handle.  The call
+ * allocates and frees nothing.  Limits: S <= GVQ_STATIC_MAX_SLICES slices and (bases x partial sums
+ * per basis) <= 65536, else GVQ_ETOOBIG; the handle's device must be the current device (GVQ_EINVAL).
+ * All calls on one GPU share the buffer, whatever the handle or stream: calls that overlap in time on
+ * one GPU race, and the buffer keeps the last call's contents (every entry a call reads it has
+ * written itself).  As for every entry point, call it once on the shapes in use before capturing it
+ * into a HIP graph.
+ */
+int gvq_local_loss_static(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out,
+                          void* stream);
 
 /*
  * Section 3, Eq. (5): for every basis of the last fit, the smallest k such that

@@ -47,6 +47,7 @@ const char* gvq_strerror(int status)
     case GVQ_ENOMEM: return "out of memory";
     case GVQ_ENONFINITE: return "fit produced a non-finite eigenvalue";
     case GVQ_ENOCONV: return "eigensolver did not converge";
+    case GVQ_ETOOBIG: return "size exceeds the static scratch buffer of this entry point";
     default: return "unknown status";
     }
 }
@@ -334,6 +335,14 @@ int gvq_local_loss(const gvq_basis_t* h, const void* grad, int n_workers, double
     if (!aligned16(grad) || ((uintptr_t)loss_out & 7u)) return GVQ_EALIGN;
     if (!h->fitted) return GVQ_ENOTFIT;
     return gvq_launch_local_loss(h, grad, n_workers, loss_out, (hipStream_t)stream);
+}
+
+int gvq_local_loss_static(const gvq_basis_t* h, const void* grad, int n_workers, double* loss_out, void* stream)
+{
+    if (!h || !grad || !loss_out || n_workers < 1) return GVQ_EINVAL;
+    if (!aligned16(grad) || ((uintptr_t)loss_out & 7u)) return GVQ_EALIGN;
+    if (!h->fitted) return GVQ_ENOTFIT;
+    return gvq_launch_local_loss_static(h, grad, n_workers, loss_out, (hipStream_t)stream);
 }
 
 int gvq_select_k(const gvq_basis_t* h, double lambda, int* k_out, void* stream)

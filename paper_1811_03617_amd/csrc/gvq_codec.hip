@@ -14,6 +14,8 @@
 // as one 128-bit word.
 #include "gvq_device.h"
 
+#include <mutex>
+
 // --------------------------------------------------------------------------------------
 // Fast phase shared by the register-resident kernels.
 //
@@ -1784,4 +1786,41 @@ static int launch_local_loss(const gvq_basis* h, const void* grad, int n_workers
 int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out, hipStream_t st)
 {
     return launch_local_loss(h, grad, n_workers, loss_out, st, h->d_loss_slice, h->d_loss_part);
+}
+
+// --------------------------------------------------------------------------------------
+// The same, for callers that cannot allocate: the scratch of the two reduction stages lives in a
+// file-scope device array instead of the handle.  In host code the array's name is only a stand-in
+// for the symbol; its device address is asked for once per device (with that device current) and
+// that pointer is what the kernels get.  Every GPU has its own copy of the array; every call on a
+// GPU shares it, so calls that overlap in time on one GPU race.  Nothing has to start at zero: the
+// kernels overwrite every entry they later read.
+// --------------------------------------------------------------------------------------
+#define GVQ_STATIC_PART_DOUBLES 65536
+static __device__ __align__(256) unsigned char scratch[sizeof(float) * GVQ_STATIC_MAX_SLICES +
+                                                        sizeof(double) * GVQ_STATIC_PART_DOUBLES];
+#define GVQ_MAX_DEVICES 64
+static void* g_scratch_ptr[GVQ_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+int gvq_launch_local_loss_static(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
+                                 hipStream_t st)
+{
+    if (h->S > GVQ_STATIC_MAX_SLICES || (int64_t)h->B * h->loss_groups > GVQ_STATIC_PART_DOUBLES) return GVQ_ETOOBIG;
+    int dev = -1;
+    GVQ_HIP(hipGetDevice(&dev));
+    if (dev != h->device || dev < 0 || dev >= GVQ_MAX_DEVICES) return GVQ_EINVAL;   // the handle's device must be current
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            GVQ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = p;
+        }
+        base = g_scratch_ptr[dev];
+    }
+    float* loss_slice = (float*)base;
+    double* loss_part = (double*)((unsigned char*)base + sizeof(float) * GVQ_STATIC_MAX_SLICES);
+    return launch_local_loss(h, grad, n_workers, loss_out, st, loss_slice, loss_part);
 }

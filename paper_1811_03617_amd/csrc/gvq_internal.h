@@ -96,6 +96,8 @@ int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_s
 int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_slice_only, hipStream_t st);
 int gvq_launch_local_loss(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
                           hipStream_t st);
+int gvq_launch_local_loss_static(const gvq_basis* h, const void* grad, int n_workers, double* loss_out,
+                                 hipStream_t st);
 int gvq_launch_layout(const void* src, void* dst, int F, int D, int HW, gvq_dtype_t dtype, bool flatten,
                       hipStream_t st);
 int gvq_launch_select_k(const gvq_basis* h, double lambda, hipStream_t st);

@@ -13,7 +13,8 @@ import numpy as np
 from . import build as _build
 
 F32, BF16 = 0, 1
-OK, EINVAL, EALIGN, ENOTFIT, EHIP, ENOMEM, ENONFINITE, ENOCONV = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EALIGN, ENOTFIT, EHIP, ENOMEM, ENONFINITE, ENOCONV, ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7, -8
+STATIC_MAX_SLICES = 1 << 21
 MAX_D = 1024
 
 _lib = None
@@ -59,6 +60,7 @@ def lib():
         L.gvq_flatten_conv.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         L.gvq_unflatten_conv.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
         L.gvq_local_loss.argtypes = [vp, vp, i32, vp, vp]
+        L.gvq_local_loss_static.argtypes = [vp, vp, i32, vp, vp]
         L.gvq_select_k.argtypes = [vp, C.c_double, C.POINTER(i32), vp]
         L.gvq_strerror.argtypes = [i32]
         L.gvq_strerror.restype = C.c_char_p
@@ -67,7 +69,7 @@ def lib():
                      "gvq_compress", "gvq_aggregate", "gvq_decompress", "gvq_basis_export",
                      "gvq_basis_export_cov", "gvq_basis_import", "gvq_set_option", "gvq_local_loss",
                      "gvq_select_k", "gvq_compress_segment", "gvq_decompress_segment", "gvq_flatten_conv",
-                     "gvq_unflatten_conv", "gvq_fit_basis_first_slice"):
+                     "gvq_unflatten_conv", "gvq_fit_basis_first_slice", "gvq_local_loss_static"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -177,6 +179,11 @@ def gvq_local_loss(h, grad, n_workers, loss_out, stream=None):
     _check(lib().gvq_local_loss(h, _ptr(grad), int(n_workers), _ptr(loss_out), _stream(stream)), "gvq_local_loss")
 
 
+def gvq_local_loss_static(h, grad, n_workers, loss_out, stream=None):
+    _check(lib().gvq_local_loss_static(h, _ptr(grad), int(n_workers), _ptr(loss_out), _stream(stream)),
+           "gvq_local_loss_static")
+
+
 def gvq_select_k(h, lam, n_bases, stream=None):
     out = (C.c_int * n_bases)()
     _check(lib().gvq_select_k(h, float(lam), out, _stream(stream)), "gvq_select_k")
@@ -243,6 +250,9 @@ class Basis:
 
     def local_loss(self, grad, n_workers, loss_out, stream=None):
         gvq_local_loss(self._h, grad, n_workers, loss_out, stream)
+
+    def local_loss_static(self, grad, n_workers, loss_out, stream=None):
+        gvq_local_loss_static(self._h, grad, n_workers, loss_out, stream)
 
     def select_k(self, lam, stream=None):
         return gvq_select_k(self._h, lam, self.B, stream)
