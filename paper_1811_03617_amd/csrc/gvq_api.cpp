@@ -66,7 +66,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_nsamp, h->d_jac, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_nsamp, h->d_bjA, h->d_bjQ, h->d_bjfro, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     for (gvq_plan& pl : h->plan) {
@@ -170,10 +170,15 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
         }
         TRY(hipMalloc((void**)&h->d_eig, sizeof(double) * B * d));
         TRY(hipMalloc((void**)&h->d_cov, sizeof(double) * B * d * d));
-        TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
         if (d > GVQ_LDS_EIGEN_MAX_D) {
-            TRY(hipMalloc((void**)&h->d_jac, sizeof(double) * B * 2 * n * n));
+            const size_t np = (size_t)gvq_bj_padded(d);
+            TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * np * np));
+            TRY(hipMalloc((void**)&h->d_bjA, sizeof(double) * B * np * np));
+            TRY(hipMalloc((void**)&h->d_bjQ, sizeof(double) * B * gvq_bj_q_doubles(d)));
+            TRY(hipMalloc((void**)&h->d_bjfro, sizeof(double) * B * (1 + 2 * 32)));   // norm, then the check's partial sums
             TRY(hipMalloc((void**)&h->d_jstate, sizeof(int) * B * 4));
+        } else {
+            TRY(hipMalloc((void**)&h->d_V, sizeof(double) * B * n * n));
         }
         if (part_doubles) {
             TRY(hipMalloc((void**)&h->d_part, sizeof(double) * B * part_doubles));

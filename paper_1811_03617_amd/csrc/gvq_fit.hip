@@ -752,7 +752,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         return gvq_launch_pack(h, st);
     }
     if (d > GVQ_LDS_EIGEN_MAX_D) {
-        const int rc = gvq_launch_eigen_large(h, L, first_slice_only, st);
+        const int rc = gvq_launch_eigen_block(h, st);
         return rc != GVQ_OK ? rc : gvq_launch_pack(h, st);
     }
     EigArgs e;
@@ -766,7 +766,7 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
                                     (int)gvq_eigen_lds_bytes(GVQ_LDS_EIGEN_MAX_D)));
         attr_set = true;
     }
-    const int threads = d > 64 ? 1024 : (d > 16 ? 256 : 64);
+    const int threads = d > 16 ? 256 : 64;
     hipLaunchKernelGGL(eigen_kernel, dim3(h->B), dim3(threads), lds, st, e);
     GVQ_HIP(hipGetLastError());
     return gvq_launch_pack(h, st);

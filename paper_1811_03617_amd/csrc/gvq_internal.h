@@ -6,7 +6,8 @@
 #include "gvq.h"
 
 #define GVQ_MAX_PTRS 32  // device pointers passed by value in one kernel launch
-#define GVQ_LDS_EIGEN_MAX_D 128  // longest slice whose d x d matrix the one-work-group eigensolver holds in LDS
+#define GVQ_LDS_EIGEN_MAX_D 64   // longest slice that goes to the one-work-group eigensolver with the matrix in LDS;
+                                 // longer ones take the block Jacobi method (gvq_eigen_block.hip)
 
 // Many bases: the split of the gradient's 16-slice tiles into super-tiles (G consecutive tiles of
 // whole slices of one basis, for the branch-free fast phase of the register-resident codec kernels)
@@ -40,15 +41,18 @@ struct gvq_basis {
     float* d_Umu = nullptr;     // [B][KP] U^T mu (bf16 gradients)
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
-    double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even
+    double* d_V = nullptr;      // [B][dp][dp] eigenvector work space, dp = d rounded up to even (block Jacobi: to
+                                // a whole number of block pairs)
     double* d_part = nullptr;   // moment partials: [B][P][packed width] for d in {16,32,64,128}, else
                                 // [B][block pairs][P][64*64+64] (64 x 64 blocks, P sample chunks)
     double* d_part2 = nullptr;  // [B][ceil(P/32)][width] second level of the partial sum (MFMA path)
     int mom_wgs = 0;            // work-groups per basis of the MFMA moments kernel (P = streams * mom_wgs there)
     double* d_mom = nullptr;    // [B][d*d+d] reduced moments (sum x x^T, then sum x)
     unsigned long long* d_nsamp = nullptr;  // [B] sample slices the moment kernels of the last fit took in, counted by them
-    double* d_jac = nullptr;    // [B][2][dp][dp] matrix buffers of the global-memory Jacobi (d > 128 only)
-    int* d_jstate = nullptr;    // [B][4] its per-basis state (d > 128 only)
+    double* d_bjA = nullptr;    // block Jacobi (d > 64): [B][n][n] the matrix, n = d padded to whole block pairs
+    double* d_bjQ = nullptr;    // [B][pairs per round][2nb][2nb] rotations of the current round
+    double* d_bjfro = nullptr;  // [B] squared Frobenius norm of the matrix, then [B][32][2] partial sums of its check
+    int* d_jstate = nullptr;    // [B][4] its per-basis state
     int* d_sweeps = nullptr;    // [B] Jacobi sweeps used, -1 = not converged
     int* d_ksel = nullptr;      // [B] result of the last gvq_select_k
     float* d_loss_slice = nullptr;  // [S] per-slice squared residual of the last gvq_local_loss
@@ -109,8 +113,7 @@ bool gvq_bf16_pipe_shape(const gvq_basis* h);
 bool gvq_moments_mfma_shape(int d);
 int gvq_moments_packed_width(int d);
 int gvq_moments_streams(int d);   // sample streams (partial slots) per work-group
-// Moments in 64 x 64 blocks (every d other than 16, 32, 64, 128); Jacobi out of global memory
-// (d > GVQ_LDS_EIGEN_MAX_D).
+// Moments in 64 x 64 blocks (every d other than 16, 32, 64, 128).
 bool gvq_long_shape(int d, int k);            // codec: the LDS-tiled MFMA kernels take this shape (d > 128, or any
                                               // shape with k <= 128 that the register-resident kernels do not)
 size_t gvq_long_pack_floats(int d, int k);    // floats per basis in either operand-order copy of U
@@ -125,4 +128,6 @@ int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t fi
 int gvq_large_groups(int d);
 size_t gvq_large_partial_doubles(int d, int chunks);   // per basis
 int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipStream_t st);
-int gvq_launch_eigen_large(gvq_basis* h, int L, bool first_slice_only, hipStream_t st);
+int gvq_bj_padded(int d);                  // block Jacobi: matrix size
+size_t gvq_bj_q_doubles(int d);            // doubles per basis of its rotation buffer
+int gvq_launch_eigen_block(gvq_basis* h, hipStream_t st);
