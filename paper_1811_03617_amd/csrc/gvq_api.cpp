@@ -131,10 +131,11 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             h->P = (int)chunks;
             part_doubles = gvq_large_partial_doubles(d, h->P);
         } else {
-            // two work-groups of 4 waves per compute unit, spread over the bases; never less
-            // than 64 sample slices per stream
+            // two work-groups of 4 waves per compute unit, spread over the bases (rounded down: every
+            // work-group runs for the whole launch, so a few more than fit would cost a second
+            // round as long as the first); never less than 64 sample slices per stream
             const int streams = gvq_moments_streams(d);
-            int64_t wgs = (2LL * h->num_cu + n_blocks - 1) / n_blocks;
+            int64_t wgs = (2LL * h->num_cu) / n_blocks;
             if (wgs > (longest + 64LL * streams - 1) / (64LL * streams)) wgs = (longest + 64LL * streams - 1) / (64LL * streams);
             if (wgs < 1) wgs = 1;
             h->mom_wgs = (int)wgs;

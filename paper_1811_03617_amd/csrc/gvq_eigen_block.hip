@@ -33,6 +33,7 @@ struct BjArgs {
     const double* mom;                 // [B][d*d+d]
     const unsigned long long* nsamp;   // [B] samples behind the moments
     int d, n, k, p;                    // p = n / 32 blocks, even
+    int cgroups;                       // work-groups per basis of the convergence check (<= BJ_CHECK_GROUPS)
     double* cov;                       // [B][d][d]
     double* A;                         // [B][n][n]
     double* V;                         // [B][n][n]
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(256) void bj_init_kernel(BjArgs a)
 }
 
 // Start of outer sweep `sweep`: stop when the off-diagonal mass is below tol^2 of the whole, on NaN,
-// or when the sweep budget is used up.  BJ_CHECK_GROUPS work-groups per basis sum a share of the rows
+// or when the sweep budget is used up.  a.cgroups work-groups per basis sum a share of the rows
 // each; the one that finishes last adds the partial sums in their fixed order and decides.
 #define BJ_CHECK_GROUPS 32
 __global__ __launch_bounds__(256) void bj_check_kernel(BjArgs a, int sweep, int max_sweeps)
@@ -98,7 +99,8 @@ __global__ __launch_bounds__(256) void bj_check_kernel(BjArgs a, int sweep, int 
     const int b = blockIdx.y, g = blockIdx.x, n = a.n, tid = threadIdx.x;
     if (a.state[4 * b]) return;
     const double* A = a.A + (size_t)b * n * n;
-    const int r0 = (int)((int64_t)n * g / BJ_CHECK_GROUPS), r1 = (int)((int64_t)n * (g + 1) / BJ_CHECK_GROUPS);
+    const int G = a.cgroups;
+    const int r0 = (int)((int64_t)n * g / G), r1 = (int)((int64_t)n * (g + 1) / G);
     double off2 = 0.0, all2 = 0.0;
     for (int i = r0 * n + tid; i < r1 * n; i += 256) {
         const int r = i / n, c = i - r * n;
@@ -117,13 +119,13 @@ __global__ __launch_bounds__(256) void bj_check_kernel(BjArgs a, int sweep, int 
         part[0] = (red_off[0] + red_off[1]) + (red_off[2] + red_off[3]);
         part[1] = (red_all[0] + red_all[1]) + (red_all[2] + red_all[3]);
         __threadfence();
-        last = atomicAdd(a.state + 4 * b + 2, 1) == BJ_CHECK_GROUPS - 1;
+        last = atomicAdd(a.state + 4 * b + 2, 1) == G - 1;
     }
     __syncthreads();
     if (!last || tid != 0) return;
     __threadfence();
     double so = 0.0, sa = 0.0;
-    for (int i = 0; i < BJ_CHECK_GROUPS; ++i) {
+    for (int i = 0; i < G; ++i) {
         const volatile double* part = a.part + ((size_t)b * BJ_CHECK_GROUPS + i) * 2;
         so += part[0];
         sa += part[1];
@@ -429,6 +431,10 @@ int gvq_launch_eigen_block(gvq_basis* h, hipStream_t st)
     a.mom = h->d_mom; a.nsamp = h->d_nsamp; a.d = d; a.n = n; a.k = h->k; a.p = p;
     a.cov = h->d_cov; a.A = h->d_bjA; a.V = h->d_V; a.Q = h->d_bjQ; a.fro2 = h->d_bjfro; a.part = h->d_bjfro + h->B;
     a.eig = h->d_eig; a.U = h->d_U; a.mu = h->d_mu; a.sweeps = h->d_sweeps; a.state = h->d_jstate; a.tol = 1e-15;
+    a.cgroups = 2 * h->num_cu / h->B;   // the check's launch fills the chip once
+    if (a.cgroups > BJ_CHECK_GROUPS) a.cgroups = BJ_CHECK_GROUPS;
+    if (a.cgroups > n / 8) a.cgroups = n / 8;
+    if (a.cgroups < 1) a.cgroups = 1;
     const size_t lds = sizeof(double) * 2 * BJ_M * BJ_LD + 2048;   // either step's matrices, the rotation parameters
     static bool attr_set = false;
     if (!attr_set) {
@@ -440,7 +446,7 @@ int gvq_launch_eigen_block(gvq_basis* h, hipStream_t st)
     GVQ_HIP(hipGetLastError());
     const int items = P2 * (P2 - 1) / 2 + (n / BJ_M) * P2;
     for (int sweep = 0; sweep <= BJ_MAX_OUTER; ++sweep) {
-        hipLaunchKernelGGL(bj_check_kernel, dim3(BJ_CHECK_GROUPS, h->B), dim3(256), 0, st, a, sweep, BJ_MAX_OUTER);
+        hipLaunchKernelGGL(bj_check_kernel, dim3(a.cgroups, h->B), dim3(256), 0, st, a, sweep, BJ_MAX_OUTER);
         GVQ_HIP(hipGetLastError());
         if (sweep == BJ_MAX_OUTER) break;
         hipLaunchKernelGGL(bj_solve_kernel, dim3(P2, h->B), dim3(256), lds, st, a, 0);

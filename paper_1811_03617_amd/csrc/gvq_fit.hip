@@ -193,6 +193,168 @@ __global__ __launch_bounds__(256, 2) void moments_mfma_kernel(MomMfmaArgs a)
     }
 }
 
+// --------------------------------------------------------------------------------------
+// d = 128: the same products with the samples staged through LDS.  The 36 tile pairs are split over
+// the four waves of a work-group (9 each: 72 accumulation registers, so two work-groups share a
+// compute unit), which all work on the SAME samples: a block of 32 consecutive slices (one contiguous
+// run of 32 * 128 elements) is loaded once with full-width loads, two blocks ahead of the one being
+// multiplied, parked in LDS as it is, and every wave fetches its operands from there -- lane (m, kk)
+// reads elements 4(m + 16q) .. +3 of sample kk of the current group of four with one LDS access and
+// has element m of tiles 4q .. 4q+3.  Each input byte crosses HBM once; one barrier per block.
+// Wave 0 (whose pairs touch every tile) also keeps the sums of x and counts the samples.
+// --------------------------------------------------------------------------------------
+#define MOM_BLOCK 32   // slices per LDS block
+
+template <bool BF16, int WAVE>
+__device__ __forceinline__ void moments128_wave(const MomMfmaArgs& a, const unsigned int* lds_u32)
+{
+    constexpr int D = 128, NTL = 8, NPAIR = 36, WP = mom_packed_width(D);
+    constexpr int P0 = 9 * WAVE, P1 = P0 + 9;
+    constexpr int ROW = BF16 ? D / 2 : D;        // 32-bit words per slice in LDS
+    const int lane = threadIdx.x & 63, tid = threadIdx.x;
+    const int m = lane & 15, kk = lane >> 4;
+    const int b = blockIdx.y, p = blockIdx.x;
+
+    const int64_t full = a.M / D;
+    int64_t lo = a.offs[b], hi = a.offs[b + 1] < full ? a.offs[b + 1] : full;
+    if (hi < lo) hi = lo;
+    const int64_t cnt = hi - lo;
+    const int64_t j0 = lo + cnt * p / a.wgs, j1 = lo + cnt * (p + 1) / a.wgs;   // this work-group's samples
+    const int64_t nblk = (j1 - j0 + MOM_BLOCK - 1) / MOM_BLOCK;
+
+    d4 acc[9];
+    double sacc[NTL];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) acc[i] = d4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < NTL; ++i) sacc[i] = 0.0;
+    unsigned int taken = 0;
+
+    // which tiles this wave's pairs touch (compile time)
+    bool need[NTL] = {false, false, false, false, false, false, false, false};
+    {
+        int pi = 0;
+#pragma unroll
+        for (int T1 = 0; T1 < NTL; ++T1)
+#pragma unroll
+            for (int T2 = T1; T2 < NTL; ++T2) {
+                if (pi >= P0 && pi < P1) { need[T1] = true; need[T2] = true; }
+                ++pi;
+            }
+    }
+
+    // a block = MOM_BLOCK slices = 128-bit words w = 0 .. WPB-1, thread t moves words t, t + 256, ...
+    constexpr int WPB = MOM_BLOCK * ROW / 4;     // 1024 (fp32) or 512 (bf16)
+    constexpr int NLD = WPB / 256;               // 4 or 2 loads per thread and block
+    mu4 stage[NLD];
+    unsigned int* ldsw = const_cast<unsigned int*>(lds_u32);
+    auto load_block = [&](const void* g, int64_t blk) {
+        const int64_t first = j0 + blk * MOM_BLOCK;                    // first slice of the block
+        const int64_t words_left = (j1 - first) * (ROW / 4);           // 128-bit words that exist
+        const mu4* src = (const mu4*)((const char*)g + first * (int64_t)(ROW * 4));
+#pragma unroll
+        for (int r = 0; r < NLD; ++r) {
+            const int wi = tid + 256 * r;
+            mu4 v = {0u, 0u, 0u, 0u};
+            if (blk < nblk && wi < words_left) v = __builtin_nontemporal_load(src + wi);
+            stage[r] = v;
+        }
+    };
+    auto park_block = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < NLD; ++r) *(mu4*)(ldsw + buf * (WPB * 4) + 4 * (tid + 256 * r)) = stage[r];
+    };
+
+    for (int l = 0; l < a.L; ++l) {
+        const void* g = a.grads.p[l];
+        if (nblk == 0) break;
+        load_block(g, 0);
+        __syncthreads();          // the previous gradient's last block is no longer being read
+        park_block(0);
+        load_block(g, 1);
+        for (int64_t blk = 0; blk < nblk; ++blk) {
+            __syncthreads();      // block blk is parked; everyone is done with the buffer that takes block blk + 1
+            if (blk + 1 < nblk) park_block((int)((blk + 1) & 1));
+            load_block(g, blk + 2);
+            const unsigned int* cur = lds_u32 + (blk & 1) * (WPB * 4);
+            const int64_t first = j0 + blk * MOM_BLOCK;
+#pragma unroll 2
+            for (int grp = 0; grp < MOM_BLOCK / 4; ++grp) {
+                const int s = 4 * grp + kk;                              // this lane's sample in the block
+                double xd[NTL];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    if (!need[4 * q] && !need[4 * q + 1] && !need[4 * q + 2] && !need[4 * q + 3]) continue;
+                    if (BF16) {
+                        const mu2 v = *(const mu2*)(cur + s * ROW + 2 * (m + 16 * q));
+                        xd[4 * q + 0] = (double)__uint_as_float(v.x << 16);
+                        xd[4 * q + 1] = (double)__uint_as_float(v.x & 0xffff0000u);
+                        xd[4 * q + 2] = (double)__uint_as_float(v.y << 16);
+                        xd[4 * q + 3] = (double)__uint_as_float(v.y & 0xffff0000u);
+                    } else {
+                        const mu4 v = *(const mu4*)(cur + s * ROW + 4 * (m + 16 * q));
+                        xd[4 * q + 0] = (double)__uint_as_float(v.x);
+                        xd[4 * q + 1] = (double)__uint_as_float(v.y);
+                        xd[4 * q + 2] = (double)__uint_as_float(v.z);
+                        xd[4 * q + 3] = (double)__uint_as_float(v.w);
+                    }
+                }
+                if (WAVE == 0) {
+#pragma unroll
+                    for (int T = 0; T < NTL; ++T) sacc[T] += xd[T];
+                    taken += (m == 0 && first + s < j1) ? 1u : 0u;
+                }
+                int pi = 0;
+#pragma unroll
+                for (int T1 = 0; T1 < NTL; ++T1)
+#pragma unroll
+                    for (int T2 = T1; T2 < NTL; ++T2) {
+                        if (pi >= P0 && pi < P1)
+                            acc[pi - P0] = __builtin_amdgcn_mfma_f64_16x16x4f64(xd[T1], xd[T2], acc[pi - P0], 0, 0, 0);
+                        ++pi;
+                    }
+            }
+        }
+    }
+
+    double* out = a.part + ((size_t)b * a.wgs + p) * WP;
+#pragma unroll
+    for (int pi = P0; pi < P1; ++pi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double* o = out + pi * 256 + r * 64 + lane;
+            *o = a.accumulate ? *o + acc[pi - P0][r] : acc[pi - P0][r];
+        }
+    if (WAVE == 0) {
+        unsigned int c = taken;
+        c += __shfl_xor(c, 16, 64);
+        c += __shfl_xor(c, 32, 64);
+        if (lane == 0 && c) atomicAdd(a.nsamp + b, (unsigned long long)c);
+#pragma unroll
+        for (int T = 0; T < NTL; ++T) {
+            double v = sacc[T];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            if (kk == 0) {
+                double* o = out + NPAIR * 256 + T * 16 + m;
+                *o = a.accumulate ? *o + v : v;
+            }
+        }
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256, 2) void moments128_kernel(MomMfmaArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned int lds[2 * MOM_BLOCK * (BF16 ? 64 : 128)];
+    switch (threadIdx.x >> 6) {
+    case 0: moments128_wave<BF16, 0>(a, lds); break;
+    case 1: moments128_wave<BF16, 1>(a, lds); break;
+    case 2: moments128_wave<BF16, 2>(a, lds); break;
+    default: moments128_wave<BF16, 3>(a, lds); break;
+    }
+}
+
 // dst[b][g][i] = src[b][g*G][i] + src[b][g*G+1][i] + ... (at most G terms, fixed order)
 __global__ void reduce_groups_kernel(const double* src, double* dst, int P, int G, int W)
 {
@@ -670,6 +832,13 @@ template <int D>
 static void launch_moments_mfma(const gvq_basis* h, const MomMfmaArgs& a, hipStream_t st)
 {
     dim3 grid(h->mom_wgs, h->B);
+    if constexpr (D == 128) {
+        if (h->dtype == GVQ_BF16)
+            hipLaunchKernelGGL((moments128_kernel<true>), grid, dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL((moments128_kernel<false>), grid, dim3(256), 0, st, a);
+        return;
+    }
     if (h->dtype == GVQ_BF16)
         hipLaunchKernelGGL((moments_mfma_kernel<D, true>), grid, dim3(256), 0, st, a);
     else
@@ -678,7 +847,7 @@ static void launch_moments_mfma(const gvq_basis* h, const MomMfmaArgs& a, hipStr
 
 bool gvq_moments_mfma_shape(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
 int gvq_moments_packed_width(int d) { return mom_packed_width(d); }
-int gvq_moments_streams(int d) { return d == 128 ? 2 : 4; }
+int gvq_moments_streams(int d) { return d == 128 ? 1 : 4; }   // d = 128: the four waves share one stream
 
 // A fill kernel rather than a memset, so that a fit can be captured into a HIP graph.
 __global__ void zero_counts_kernel(unsigned long long* p, int n)
