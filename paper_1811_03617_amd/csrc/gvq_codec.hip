@@ -99,10 +99,12 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
 
     u4 regs[NL];
     f4 prev[RING ? NSO : 1];
-    auto load_super = [&](int64_t t0) {
+    // stride = 1024: the super-tile's NL rows of 1 KB; stride = 0 (no next super-tile: the loads stay so
+    // that they can be counted, but all fetch one row that was just read)
+    auto load_super = [&](int64_t t0, int stride) {
         const char* base = (const char*)a.in + t0 * (int64_t)(TILE_SLICES * D) * (BF16 ? 2 : 4) + lane * 16;
 #pragma unroll
-        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * 1024));
+        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * stride));
         if constexpr (RING) {
             const float* pin = a.acc_in + t0 * TILE_SLICES * a.k;
 #pragma unroll
@@ -112,7 +114,7 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
 
     int64_t cur = it.p;
     int b = super_basis<MANY>(a, cur);
-    load_super(super_tile<G, MANY>(a, cur));
+    load_super(super_tile<G, MANY>(a, cur), 1024);
     for (;;) {
         load_basis(b);
         drain_memory();
@@ -148,7 +150,7 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
 #pragma unroll
                 for (int r = 0; r < NSO; ++r) pv[r] = prev[r];
             }
-            load_super(tn);   // the next super-tile (or this one again, unused, when there is none)
+            load_super(tn, more ? 1024 : 0);   // the next super-tile (or one row of this one, unused, when there is none)
             wave_lds_sync();
             f4 x[G][NQ];
 #pragma unroll
@@ -544,10 +546,10 @@ __device__ __forceinline__ void compress_bf16_fast_phase(const CodecArgs& a, u4*
     };
     u4 regs[NL];
     f4 prev[ACC ? NSO : 1];
-    auto load_super = [&](int64_t t0) {
+    auto load_super = [&](int64_t t0, int stride) {   // stride: see compress_fast_phase
         const char* base = (const char*)a.in + t0 * (int64_t)(TILE_SLICES * D) * 2 + lane * 16;
 #pragma unroll
-        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * 1024));
+        for (int r = 0; r < NL; ++r) regs[r] = stream_load((const u4*)(base + r * stride));
         if constexpr (ACC) {
             const float* pin = a.acc_in + t0 * TILE_SLICES * a.k;
 #pragma unroll
@@ -557,7 +559,7 @@ __device__ __forceinline__ void compress_bf16_fast_phase(const CodecArgs& a, u4*
 
     int64_t cur = it.p;
     int b = super_basis<MANY>(a, cur);
-    load_super(super_tile<G, MANY>(a, cur));
+    load_super(super_tile<G, MANY>(a, cur), 1024);
     for (;;) {
         load_basis(b);
         drain_memory();
@@ -578,7 +580,7 @@ __device__ __forceinline__ void compress_bf16_fast_phase(const CodecArgs& a, u4*
 #pragma unroll
                 for (int r = 0; r < NSO; ++r) pv[r] = prev[r];
             }
-            load_super(tn);
+            load_super(tn, more ? 1024 : 0);
             wave_lds_sync();
             u4 xb[G][NST];
 #pragma unroll
