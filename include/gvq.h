@@ -71,6 +71,11 @@ typedef enum {
  * the whole gradient (n_blocks must then be 1).  Allocates the device copies of U, mu,
  * eig and the fit scratch on the current device.  Section 2 (slicing; one compressor per
  * group of slices, Section 3 "compressor reuse").
+ * Speed by shape: d in {16,32,64,128} with k <= 32 runs register-resident kernels; every other
+ * shape runs LDS-tiled kernels that take 128 comps per pass over the gradient, so k > 128 costs
+ * ceil(k/128) passes (compress, and decompress to fp32).  Two calls keep slow any-shape kernels
+ * when k > 128: decompress to bf16 output and gvq_local_loss.  The paper's setting (compression
+ * ratio d/k >= 8, Section 4) never reaches k > 128 at d <= GVQ_MAX_D.
  */
 int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blocks,
                      const int64_t* block_slice_offsets, gvq_dtype_t grad_dtype);

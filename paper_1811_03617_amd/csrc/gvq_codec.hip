@@ -1604,7 +1604,9 @@ static int launch_decompress_d(const gvq_basis* h, const CodecArgs& a, hipStream
 int gvq_launch_decompress(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                           void* out, gvq_dtype_t odt, hipStream_t st)
 {
-    if (gvq_long_shape(h->d, h->k)) return gvq_launch_decompress_long(h, comp, first_slice, n_slices, out, odt, st);
+    // (bf16 output of more than 128 comps cannot add up its column passes in place: the any-shape kernel below)
+    if (gvq_long_shape(h->d, h->k) && !(h->k > 128 && odt == GVQ_BF16))
+        return gvq_launch_decompress_long(h, comp, first_slice, n_slices, out, odt, st);
     CodecArgs a = make_args(h, comp, out, 1, h->d_Upd);
     a.seg_begin = first_slice; a.seg_end = first_slice + n_slices;
     const bool bf = odt == GVQ_BF16;
@@ -1758,7 +1760,7 @@ static int launch_local_loss(const gvq_basis* h, const void* grad, int n_workers
     a.Upack2 = (const f4*)h->d_Upd;
     const bool bf = h->dtype == GVQ_BF16;
     int rc = GVQ_OK;
-    if (gvq_long_shape(h->d, h->k)) {
+    if (gvq_long_shape(h->d, h->k) && h->k <= 128) {
         rc = gvq_launch_loss_long(h, grad, n_workers, loss_slice, st);
     } else if (gvq_mfma_shape(h->d, h->k)) {
         switch (h->d) {

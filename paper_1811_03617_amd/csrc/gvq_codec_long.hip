@@ -26,7 +26,10 @@ struct LongArgs {
     const int64_t* offs;     // [B+1]
     const int64_t* tstart;   // [B+1] first tile of each basis (B > 1 only)
     int64_t M, S, seg_begin, seg_end, t0, t1;
-    int B, d, k, nchunk;
+    int B, d, k, nchunk;     // k: the comps of THIS column pass (at most 128)
+    int kfull, c0;           // row length of the compressed vector, first comp of this pass (k > 128: several passes)
+    int accum;               // decompress: add to what grad_out holds (passes after the first; fp32 output only)
+    int upack_stride;        // packed-U words (f4 / u4) from one basis to the next
     float n_workers;
 };
 
@@ -90,8 +93,8 @@ __device__ __forceinline__ void store_y4(const LongArgs& a, int64_t s, int c0, f
 {
     if (c0 >= a.k) return;
     float* Y = (float*)a.out;
-    const int64_t o = s * a.k + c0;
-    if ((a.k & 3) == 0) {
+    const int64_t o = s * a.kfull + a.c0 + c0;
+    if ((a.kfull & 3) == 0) {
         if (a.acc_in) v += *(const f4*)(a.acc_in + o);
         *(f4*)(Y + o) = v;
     } else {
@@ -107,6 +110,17 @@ template <bool OUT_BF16>
 __device__ __forceinline__ void store_x4(const LongArgs& a, bool vec, int64_t s, int e0, f4 v)
 {
     const int64_t idx = s * a.d + e0;
+    if (!OUT_BF16 && a.accum) {   // a later column pass: add to the earlier passes' sum
+        if (vec) {
+            f4* o = (f4*)((float*)a.out + idx);
+            *o = *o + v;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (e0 + r < a.d && idx + r < a.M) ((float*)a.out)[idx + r] += v[r];
+        }
+        return;
+    }
     if (vec) {
         if (OUT_BF16) {
             u2 w2;
@@ -314,14 +328,14 @@ __global__ __launch_bounds__(256, 2) void compress_long_kernel(LongArgs a)
         int64_t first, end;
         long_tile(a, tile, b, first, end);
         const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
-        const f4* Ub = a.Upack + (size_t)b * a.nchunk * CH4;
+        const f4* Ub = a.Upack + (size_t)b * a.upack_stride;
         __syncthreads();   // the previous tile's readers are done with mus and Us
         for (int e = tid; e < a.nchunk * LC; e += 256)
             mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] / a.n_workers : 0.f;
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
         __syncthreads();
-        const f4* Ub2 = LOSS ? a.Upack2 + (size_t)b * a.nchunk * CH4 : nullptr;
+        const f4* Ub2 = LOSS ? a.Upack2 + (size_t)b * a.upack_stride : nullptr;
         if ((a.d & 3) == 0 && end * a.d <= a.M)
             compress_long_tile<NT, BF16, true, LOSS>(a, Us, mus, Ub, Ub2, first, end, lo, hi);
         else
@@ -352,9 +366,9 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
         int64_t first, end;
         long_tile(a, tile, b, first, end);
         const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
-        const f4* Ub = a.Upack + (size_t)b * a.nchunk * CH4;
+        const f4* Ub = a.Upack + (size_t)b * a.upack_stride;
         __syncthreads();
-        for (int e = tid; e < a.nchunk * LC; e += 256) mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] : 0.f;
+        for (int e = tid; e < a.nchunk * LC; e += 256) mus[e] = (e < a.d && !a.accum) ? a.mu[(size_t)b * a.d + e] : 0.f;
         f4 ur[NT];
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
@@ -372,8 +386,8 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
                 yr[t][w] = f4{0.f, 0.f, 0.f, 0.f};
                 const int c0 = 16 * w + 4 * kk;
                 if (!ok[t] || c0 >= a.k) continue;
-                const float* p = Y + s[t] * a.k + c0;
-                if ((a.k & 3) == 0) {
+                const float* p = Y + s[t] * a.kfull + a.c0 + c0;
+                if ((a.kfull & 3) == 0) {
                     yr[t][w] = *(const f4*)p;
                 } else {
 #pragma unroll
@@ -567,7 +581,7 @@ __global__ __launch_bounds__(256, 2) void compress_split_kernel(LongArgs a)
         int64_t first, end;
         long_tile(a, tile, b, first, end);
         const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
-        const u4* Ub = (const u4*)a.Upack + (size_t)b * a.nchunk * CH4;
+        const u4* Ub = (const u4*)a.Upack + (size_t)b * a.upack_stride;
         __syncthreads();
         for (int e = tid; e < a.nchunk * LC; e += 256)
             mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] / a.n_workers : 0.f;
@@ -597,9 +611,9 @@ __global__ __launch_bounds__(256, 2) void decompress_split_kernel(LongArgs a)
         int64_t first, end;
         long_tile(a, tile, b, first, end);
         const int64_t lo = first > a.seg_begin ? first : a.seg_begin, hi = end < a.seg_end ? end : a.seg_end;
-        const u4* Ub = (const u4*)a.Upack + (size_t)b * a.nchunk * CH4;
+        const u4* Ub = (const u4*)a.Upack + (size_t)b * a.upack_stride;
         __syncthreads();
-        for (int e = tid; e < a.nchunk * LC; e += 256) mus[e] = e < a.d ? a.mu[(size_t)b * a.d + e] : 0.f;
+        for (int e = tid; e < a.nchunk * LC; e += 256) mus[e] = (e < a.d && !a.accum) ? a.mu[(size_t)b * a.d + e] : 0.f;
         u4 ur[NT];
 #pragma unroll
         for (int q = 0; q < NT; ++q) Us[tid + 256 * q] = Ub[tid + 256 * q];
@@ -620,8 +634,8 @@ __global__ __launch_bounds__(256, 2) void decompress_split_kernel(LongArgs a)
                     v[h] = f4{0.f, 0.f, 0.f, 0.f};
                     const int c0 = 32 * ks + 8 * kk + 4 * h;
                     if (!ok[t] || c0 >= a.k) continue;
-                    const float* p = Y + s[t] * a.k + c0;
-                    if ((a.k & 3) == 0) {
+                    const float* p = Y + s[t] * a.kfull + a.c0 + c0;
+                    if ((a.kfull & 3) == 0) {
                         v[h] = *(const f4*)p;
                     } else {
 #pragma unroll
@@ -683,17 +697,19 @@ __global__ __launch_bounds__(256, 2) void decompress_split_kernel(LongArgs a)
 // The two-term bf16 copies of U for the split kernels, 8 values per 128-bit word in operand order
 // (layouts above); term 0 = bf16(U), term 1 = bf16(U - term 0); zero where e >= d or comp >= k.
 __global__ void pack_long_split_kernel(const float* U, unsigned short* Upc, unsigned short* Upd, int d, int k, int NT,
-                                       int nchunk)
+                                       int nchunk, int c0, int npass, int pass)
 {
     const int b = blockIdx.y, NKS = NT / 2;
-    const float* Ub = U + (size_t)b * d * k;
-    const size_t per = (size_t)nchunk * 4 * NT * 64 * 8;   // bf16 values per basis in either copy
+    const float* Ub = U + (size_t)b * d * k + c0;          // this column pass starts at comp c0
+    const size_t per = (size_t)nchunk * 4 * NT * 64 * 8;   // bf16 values per basis and pass in either copy
+    Upc += ((size_t)b * npass + pass) * per - (size_t)b * per;
+    Upd += ((size_t)b * npass + pass) * per - (size_t)b * per;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < per; i += (size_t)gridDim.x * blockDim.x) {
         const int j = (int)(i & 7), lane = (int)((i >> 3) & 63), m = lane & 15, kk = lane >> 4;
         const size_t word = i >> 9;                         // index of the 64-lane word group
         const int c = (int)(word / (4 * NT)), w = (int)(word % (4 * NT));
         auto term = [&](int e, int comp, int p) -> unsigned short {
-            if (e >= d || comp >= k) return 0;
+            if (e >= d || c0 + comp >= k) return 0;
             const float u = Ub[(size_t)e * k + comp];
             const unsigned int t0 = f32_to_bf16_rne(u);
             if (p == 0) return (unsigned short)t0;
@@ -711,22 +727,25 @@ __global__ void pack_long_split_kernel(const float* U, unsigned short* Upc, unsi
 }
 
 // Upc / Upd for the kernels above; one thread per float, zero where e >= d or comp >= k.
-__global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, int k, int NT, int nchunk)
+__global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, int k, int NT, int nchunk, int c0,
+                                 int npass, int pass)
 {
     const int b = blockIdx.y;
-    const float* Ub = U + (size_t)b * d * k;
-    const size_t per = (size_t)nchunk * 4 * NT * 64 * 4;   // floats per basis in either copy
+    const float* Ub = U + (size_t)b * d * k + c0;          // this column pass starts at comp c0
+    const size_t per = (size_t)nchunk * 4 * NT * 64 * 4;   // floats per basis and pass in either copy
+    Upc += ((size_t)b * npass + pass) * per - (size_t)b * per;
+    Upd += ((size_t)b * npass + pass) * per - (size_t)b * per;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < per; i += (size_t)gridDim.x * blockDim.x) {
         const int j = (int)(i & 3), lane = (int)((i >> 2) & 63), m = lane & 15, kk = lane >> 4;
         const size_t hi = i >> 8;
         const int inner = (int)(hi % NT), outer = (int)((hi / NT) & 3), c = (int)(hi / (4 * NT));
         {   // compress order: outer = i (load), inner = nt
             const int e = c * LC + LWORD(outer, kk) + j, comp = 16 * inner + m;
-            Upc[(size_t)b * per + i] = (e < d && comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
+            Upc[(size_t)b * per + i] = (e < d && c0 + comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
         }
         {   // decompress order: outer = et, inner = w
             const int e = c * LC + 16 * outer + m, comp = 16 * inner + 4 * kk + j;
-            Upd[(size_t)b * per + i] = (e < d && comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
+            Upd[(size_t)b * per + i] = (e < d && c0 + comp < k) ? Ub[(size_t)e * k + comp] : 0.0f;
         }
     }
 }
@@ -734,16 +753,29 @@ __global__ void pack_long_kernel(const float* U, float* Upc, float* Upd, int d, 
 // ======================================================================================
 // host side
 // ======================================================================================
-// Every shape the register-resident kernels for d in {16,32,64,128}, k <= 32 do not take.
-bool gvq_long_shape(int d, int k) { return k <= 128 && !gvq_mfma_shape(d, k); }
+// Every shape the register-resident kernels for d in {16,32,64,128}, k <= 32 do not take.  A kernel launch
+// handles at most 128 comps (8 column tiles of 16); more than that takes ceil(k / 128) column passes
+// over the gradient: each compress pass writes its own comps, each decompress pass after the first adds
+// to the reconstruction so far (fp32 output; bf16 output of k > 128 keeps the any-shape kernel).
+bool gvq_long_shape(int d, int k) { return !gvq_mfma_shape(d, k); }
+int gvq_long_passes(int k) { return (k + 127) / 128; }
 int gvq_long_nt(int k) { return k <= 16 ? 1 : k <= 32 ? 2 : k <= 64 ? 4 : k <= 96 ? 6 : 8; }
 int gvq_long_chunks(int d) { return (d + LC - 1) / LC; }
-size_t gvq_long_pack_floats(int d, int k) { return (size_t)gvq_long_chunks(d) * LC * 16 * gvq_long_nt(k); }
 int64_t gvq_long_tiles(int64_t slices) { return (slices + LW_SLICES - 1) / LW_SLICES; }
 
-static int split_nt(int k) { const int nt = gvq_long_nt(k); return nt < 2 ? 2 : nt; }
-// bf16 values per basis in either split copy of U
-size_t gvq_long_split_pack_halves(int d, int k) { return (size_t)gvq_long_chunks(d) * 4 * split_nt(k) * 64 * 8; }
+static int pass_k(int k, int pass) { return k - 128 * pass < 128 ? k - 128 * pass : 128; }
+static int pack_nt(int k) { return k > 128 ? 8 : gvq_long_nt(k); }          // column tiles per pass as packed
+static int split_nt(int k) { const int nt = pack_nt(k); return nt < 2 ? 2 : nt; }
+// floats per basis in either operand-order copy of U (all passes)
+size_t gvq_long_pack_floats(int d, int k)
+{
+    return (size_t)gvq_long_passes(k) * gvq_long_chunks(d) * LC * 16 * pack_nt(k);
+}
+// bf16 values per basis in either split copy of U (all passes)
+size_t gvq_long_split_pack_halves(int d, int k)
+{
+    return (size_t)gvq_long_passes(k) * gvq_long_chunks(d) * 4 * split_nt(k) * 64 * 8;
+}
 
 // Which matrix pipe: exact fp32 products while they keep up with memory (2dk / (4(d + k)) below 10
 // flop per byte; at 14, d = 256 and k = 32, the fp32 decompress already falls a quarter behind the
@@ -754,19 +786,22 @@ bool gvq_long_split(const gvq_basis* h)
     const int mode = gvq_opt_long_mode();
     if (mode == 1) return false;
     if (mode == 2) return true;
-    return 2.0 * h->d * h->k / (4.0 * (h->d + h->k)) >= 10.0;
+    const int k = h->k < 128 ? h->k : 128;   // per pass
+    return 2.0 * h->d * k / (4.0 * (h->d + k)) >= 10.0;
 }
 
 int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st)
 {
-    const int NT = gvq_long_nt(h->k), nchunk = gvq_long_chunks(h->d);
-    hipLaunchKernelGGL(pack_long_kernel, dim3(64, h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd, h->d, h->k,
-                       NT, nchunk);
-    GVQ_HIP(hipGetLastError());
+    const int nchunk = gvq_long_chunks(h->d), np = gvq_long_passes(h->k);
     unsigned short* Upd = h->d_Upb + (size_t)h->B * gvq_long_split_pack_halves(h->d, h->k);
-    hipLaunchKernelGGL(pack_long_split_kernel, dim3(64, h->B), dim3(256), 0, st, h->d_U, h->d_Upb, Upd, h->d, h->k,
-                       split_nt(h->k), nchunk);
-    GVQ_HIP(hipGetLastError());
+    for (int p = 0; p < np; ++p) {
+        hipLaunchKernelGGL(pack_long_kernel, dim3(64, h->B), dim3(256), 0, st, h->d_U, h->d_Upc, h->d_Upd, h->d, h->k,
+                           pack_nt(h->k), nchunk, 128 * p, np, p);
+        GVQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(pack_long_split_kernel, dim3(64, h->B), dim3(256), 0, st, h->d_U, h->d_Upb, Upd, h->d, h->k,
+                           split_nt(h->k), nchunk, 128 * p, np, p);
+        GVQ_HIP(hipGetLastError());
+    }
     return GVQ_OK;
 }
 
@@ -790,7 +825,21 @@ static LongArgs long_args(const gvq_basis* h, const void* in, void* out, const f
     a.t0 = tile_of_slice(h, a.seg_begin);
     a.t1 = tile_of_slice(h, a.seg_end - 1) + 1;
     a.B = h->B; a.d = h->d; a.k = h->k; a.nchunk = gvq_long_chunks(h->d);
+    a.kfull = h->k; a.c0 = 0; a.accum = 0; a.upack_stride = 0;
     a.n_workers = 1.f;
+    return a;
+}
+
+// Arguments of column pass `pass`: its comps, and its packed U (`upack`: the copy of all bases and passes,
+// nt column tiles per pass as packed; both copies count 4 * nt * 64 128-bit words per chunk).
+static LongArgs pass_args(const gvq_basis* h, const LongArgs& a0, const void* upack, int nt, int pass)
+{
+    LongArgs a = a0;
+    const size_t per = (size_t)a.nchunk * 4 * nt * 64;
+    a.k = pass_k(h->k, pass);
+    a.c0 = 128 * pass;
+    a.upack_stride = (int)(per * gvq_long_passes(h->k));
+    a.Upack = (const f4*)upack + per * pass;
     return a;
 }
 
@@ -874,39 +923,56 @@ static int decompress_split_nt(const gvq_basis* h, const LongArgs& a, int NT, hi
 int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
                              int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
-    LongArgs a = long_args(h, grad, out, h->d_Upc, first_slice, n_slices);
-    a.acc_in = comp_in;
-    a.n_workers = (float)n_workers;
-    if (gvq_long_split(h)) {
-        a.Upack = (const f4*)h->d_Upb;
-        return h->dtype == GVQ_BF16 ? compress_split_nt<true>(h, a, split_nt(h->k), st)
-                                    : compress_split_nt<false>(h, a, split_nt(h->k), st);
+    LongArgs a0 = long_args(h, grad, out, h->d_Upc, first_slice, n_slices);
+    a0.acc_in = comp_in;
+    a0.n_workers = (float)n_workers;
+    const bool split = gvq_long_split(h), bf = h->dtype == GVQ_BF16;
+    for (int p = 0; p < gvq_long_passes(h->k); ++p) {
+        int rc;
+        if (split) {
+            const LongArgs a = pass_args(h, a0, h->d_Upb, split_nt(h->k), p);
+            rc = bf ? compress_split_nt<true>(h, a, split_nt(h->k), st) : compress_split_nt<false>(h, a, split_nt(h->k), st);
+        } else {
+            const LongArgs a = pass_args(h, a0, h->d_Upc, pack_nt(h->k), p);
+            rc = bf ? compress_long_nt<true, false>(h, a, pack_nt(h->k), st)
+                    : compress_long_nt<false, false>(h, a, pack_nt(h->k), st);
+        }
+        if (rc != GVQ_OK) return rc;
     }
-    const int NT = gvq_long_nt(h->k);
-    return h->dtype == GVQ_BF16 ? compress_long_nt<true, false>(h, a, NT, st)
-                                : compress_long_nt<false, false>(h, a, NT, st);
+    return GVQ_OK;
 }
 
-// Per-slice squared residuals of Eq. (6) into loss_slice[S]; the caller sums them per basis.
+// Per-slice squared residuals of Eq. (6) into loss_slice[S]; the caller sums them per basis.  k <= 128.
 int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, float* loss_slice, hipStream_t st)
 {
-    LongArgs a = long_args(h, grad, loss_slice, h->d_Upc, 0, h->S);
-    a.Upack2 = (const f4*)h->d_Upd;
-    a.n_workers = (float)n_workers;
+    LongArgs a0 = long_args(h, grad, loss_slice, h->d_Upc, 0, h->S);
+    a0.n_workers = (float)n_workers;
     const int NT = gvq_long_nt(h->k);
+    LongArgs a = pass_args(h, a0, h->d_Upc, NT, 0);
+    a.Upack2 = (const f4*)h->d_Upd;
     return h->dtype == GVQ_BF16 ? compress_long_nt<true, true>(h, a, NT, st)
                                 : compress_long_nt<false, true>(h, a, NT, st);
 }
 
+// k > 128 needs fp32 output (the passes add up in grad_out).
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                                void* out, gvq_dtype_t odt, hipStream_t st)
 {
-    LongArgs a = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
-    if (gvq_long_split(h)) {
-        a.Upack = (const f4*)(h->d_Upb + (size_t)h->B * gvq_long_split_pack_halves(h->d, h->k));
-        return odt == GVQ_BF16 ? decompress_split_nt<true>(h, a, split_nt(h->k), st)
-                               : decompress_split_nt<false>(h, a, split_nt(h->k), st);
+    const LongArgs a0 = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
+    const bool split = gvq_long_split(h), bf = odt == GVQ_BF16;
+    const unsigned short* Upd_split = h->d_Upb + (size_t)h->B * gvq_long_split_pack_halves(h->d, h->k);
+    for (int p = 0; p < gvq_long_passes(h->k); ++p) {
+        int rc;
+        if (split) {
+            LongArgs a = pass_args(h, a0, Upd_split, split_nt(h->k), p);
+            a.accum = p > 0;
+            rc = bf ? decompress_split_nt<true>(h, a, split_nt(h->k), st) : decompress_split_nt<false>(h, a, split_nt(h->k), st);
+        } else {
+            LongArgs a = pass_args(h, a0, h->d_Upd, pack_nt(h->k), p);
+            a.accum = p > 0;
+            rc = bf ? decompress_long_nt<true>(h, a, pack_nt(h->k), st) : decompress_long_nt<false>(h, a, pack_nt(h->k), st);
+        }
+        if (rc != GVQ_OK) return rc;
     }
-    const int NT = gvq_long_nt(h->k);
-    return odt == GVQ_BF16 ? decompress_long_nt<true>(h, a, NT, st) : decompress_long_nt<false>(h, a, NT, st);
+    return GVQ_OK;
 }

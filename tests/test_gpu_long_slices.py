@@ -1,6 +1,7 @@
 """Slices longer than 128 elements (Section 3, "slice size": a multiple of filters x depth, 768
-in the paper's example): the basis refresh runs its moments in 64 x 64 blocks and its Jacobi out
-of global memory, the codec runs the any-shape kernels.  Same parity bar as the short slices."""
+in the paper's example): the basis refresh runs its moments in 64 x 64 blocks and a block Jacobi
+eigensolver, the codec runs the LDS-tiled long-slice kernels, one pass per 128 comps of a slice.
+Same parity bar as the short slices."""
 import numpy as np
 import pytest
 
@@ -206,6 +207,10 @@ def _check_codec(w, out_dtype=None):
     (129 * 400 + 128, 129, 3, 2, "bf16", 129 * 100),
     (300, 512, 8, 2, "f32", 0),                      # a single partial slice
     (256 * 10 * 40 + 77, 256, 24, 2, "f32", 256 * 10),   # 41 bases of 10 slices: every tile mostly empty
+    (512 * 300 + 100, 512, 256, 3, "f32", 0),        # more than 128 comps: two column passes
+    (320 * 500 + 3, 320, 200, 2, "f32", 320 * 150),  # 128 + 72 comps, several bases
+    (256 * 260 + 5, 256, 131, 2, "bf16", 0),         # second pass of 3 comps, k not a multiple of 4
+    (1024 * 70 + 9, 1024, 520, 2, "f32", 0),         # five passes, the last of 8 comps
 ])
 @pytest.mark.parametrize("pipe", [1, 2], ids=["fp32-products", "bf16-split-products"])
 def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):

@@ -29,6 +29,8 @@ CASES = [
     # long slices: 128-slice work-group tiles that never straddle two bases
     (256 * 700 + 40, 256, 32, "f32", 0), (320 * 500 + 9, 320, 40, "bf16", 320 * 130),
     (192 * 300 + 5, 192, 7, "f32", 192 * 100),
+    # more than 128 comps per slice: one pass of the long-slice kernels per 128 columns
+    (512 * 200 + 9, 512, 200, "f32", 0), (256 * 300 + 5, 256, 130, "bf16", 256 * 100),
 ]
 
 
