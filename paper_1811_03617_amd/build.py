@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgvq.so")
-SOURCES = ["gvq_api.cpp", "gvq_codec.hip", "gvq_codec_long.hip", "gvq_fit.hip", "gvq_fit_large.hip", "gvq_eigen_block.hip", "gvq_layout.hip"]
+SOURCES = ["gvq_api.cpp", "gvq_codec.hip", "gvq_codec_long.hip", "gvq_codec_ws.hip", "gvq_fit.hip", "gvq_fit_large.hip", "gvq_eigen_block.hip", "gvq_layout.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -40,7 +40,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     try:
         objs = [os.path.join(tmp, s + ".o") for s in SOURCES]
-        with concurrent.futures.ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as pool:
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
             jobs = [pool.submit(run, [*common, "-c", "-o", o, os.path.join(CSRC, s)]) for s, o in zip(SOURCES, objs)]
             for j in jobs:
                 j.result()

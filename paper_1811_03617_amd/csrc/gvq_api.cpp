@@ -56,7 +56,7 @@ int gvq_set_option(int option, int value)
 {
     if (option == 0 && value >= 0 && value <= 64) { g_wg_per_cu = value; return GVQ_OK; }
     if (option == 1 && value >= 0) { g_run_tiles = value; return GVQ_OK; }
-    if (option == 2 && value >= 0 && value <= 2) { g_long_mode = value; return GVQ_OK; }
+    if (option == 2 && value >= 0 && value <= 3) { g_long_mode = value; return GVQ_OK; }
     if (option == 3 && value >= 0 && value <= 7) { g_no_fast = value; return GVQ_OK; }
     if (option == 4 && value >= -1 && value <= 7) { g_pace = value; return GVQ_OK; }
     return GVQ_EINVAL;
@@ -66,7 +66,7 @@ int gvq_basis_destroy(gvq_basis_t* h)
 {
     if (!h) return GVQ_OK;
     (void)hipDeviceSynchronize();
-    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_nsamp, h->d_bjA, h->d_bjQ, h->d_bjfro, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
+    void* dev[] = {h->d_offs, h->d_tile_block, h->d_U, h->d_Upc, h->d_Upd, h->d_Upb, h->d_Uws, h->d_Umu, h->d_mu, h->d_eig, h->d_cov, h->d_V, h->d_part, h->d_part2, h->d_mom, h->d_nsamp, h->d_bjA, h->d_bjQ, h->d_bjfro, h->d_jstate, h->d_ltile, h->d_sweeps, h->d_ksel, h->d_loss_slice, h->d_loss_part};
     for (void* p : dev)
         if (p) (void)hipFree(p);
     for (gvq_plan& pl : h->plan) {
@@ -151,6 +151,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * pf));
             TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * pf));
             TRY(hipMalloc((void**)&h->d_Upb, sizeof(unsigned short) * B * 2 * gvq_long_split_pack_halves(d, k)));
+            if (gvq_ws_shape(h)) TRY(hipMalloc((void**)&h->d_Uws, sizeof(unsigned short) * gvq_ws_pack_halves(d, k)));
             if (n_blocks > 1) {
                 h->h_ltile = (int64_t*)malloc(sizeof(int64_t) * (B + 1));
                 if (!h->h_ltile) { rc = GVQ_ENOMEM; goto fail; }

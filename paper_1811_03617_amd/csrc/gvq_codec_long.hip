@@ -14,7 +14,7 @@
 #define LW_SLICES 128
 #define LC 64
 // first element (inside a chunk) of word i of lane group kk in the compress kernels
-#define LWORD(i, kk) (32 * ((i) >> 1) + 8 * (kk) + 4 * ((i) & 1))
+#define LWORD(i, kk) (32 * ((i) >> 1) + 16 * ((i) & 1) + 4 * (kk))
 
 struct LongArgs {
     const void* in;
@@ -143,9 +143,9 @@ __device__ __forceinline__ void store_x4(const LongArgs& a, bool vec, int64_t s,
 // --------------------------------------------------------------------------------------
 // compress: D[comp][slice] += U[elem][comp] x[slice][elem].  For chunk c, word i (0..3) and
 // step j (0..3), lane (m, kk) of the A operand holds U[64c + w(i, kk) + j][16nt + m] and lane
-// (n, kk) of the B operand x[slice n][64c + w(i, kk) + j] - mu/N with w(i, kk) = 32(i/2) + 8kk +
-// 4(i%2): one 128-bit word of x feeds four steps, and a lane's two words of a pair are
-// adjacent, so that the four lanes of a slice read 128 contiguous bytes.  Result register r of
+// (n, kk) of the B operand x[slice n][64c + w(i, kk) + j] - mu/N with w(i, kk) = 32(i/2) + 16(i%2)
+// + 4kk: one 128-bit word of x feeds four steps, and the four lanes of a slice read 64 contiguous
+// bytes per load instruction (the order of the contraction is free).  Result register r of
 // lane (n, kk) is comp 16nt + 4kk + r of slice n.
 // Upack[b][c][i][nt][lane] = the four U values (j = 0..3) of that lane, zero past d and k.
 // --------------------------------------------------------------------------------------
@@ -463,26 +463,14 @@ __global__ __launch_bounds__(256, 2) void decompress_long_kernel(LongArgs a)
 // bound by memory again.  U is split once per basis (pack_long_split_kernel), x (after x - mu/N)
 // and Y in registers.  Tiling, U streaming through LDS and tile ownership are as above; NT is
 // even here (an MFMA step of decompress contracts 32 comps).
-//   compress:   chunk c, step st (0,1): A lane (m, kk) = U[64c + 32st + 8kk + j][16nt + m], j = 0..7,
-//               B lane (n, kk) = x[slice n][64c + 32st + 8kk + j];
+//   compress:   chunk c, step st (0,1): A lane (m, kk) = U[64c + 32st + r(kk, j)][16nt + m], j = 0..7,
+//               B lane (n, kk) = x[slice n][64c + 32st + r(kk, j)], r(kk, j) = 16(j/4) + 4kk + j%4: the
+//               contraction order is free, and this one makes the four lanes of a slice read 64
+//               contiguous bytes per load instruction;
 //               Upack[b][c][st][p][nt][lane] = 8 bf16 of term p;
-//   decompress: chunk c, element tile et, comp step ks: A lane (m, kk) = U[64c + 16et + m][32ks + 8kk + j],
-//               B lane (n, kk) = Y[slice n][32ks + 8kk + j];  Upack[b][c][et][ks][p][lane].
+//   decompress: chunk c, element tile et, comp step ks: A lane (m, kk) = U[64c + 16et + m][32ks + r(kk, j)],
+//               B lane (n, kk) = Y[slice n][32ks + r(kk, j)];  Upack[b][c][et][ks][p][lane].
 // ======================================================================================
-typedef __bf16 lbf8 __attribute__((ext_vector_type(8)));
-
-// 8 floats -> their two bf16 terms, packed in operand order (element 2i in the low half of word i)
-__device__ __forceinline__ void split8(const f4& v0, const f4& v1, u4& hi, u4& lo)
-{
-    float r[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const unsigned int h = pack_bf16x2(r[2 * i], r[2 * i + 1]);
-        hi[i] = h;
-        lo[i] = pack_bf16x2(r[2 * i] - __uint_as_float(h << 16), r[2 * i + 1] - __uint_as_float(h & 0xffff0000u));
-    }
-}
-
 template <int NT, bool BF16, bool FAST>
 __device__ __forceinline__ void compress_split_tile(const LongArgs& a, u4* Us, const float* mus, const u4* Ub,
                                                     int64_t first, int64_t end, int64_t lo, int64_t hi)
@@ -506,7 +494,7 @@ __device__ __forceinline__ void compress_split_tile(const LongArgs& a, u4* Us, c
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[t][nt] = f4{0.f, 0.f, 0.f, 0.f};
     const int last = a.nchunk - 1;
-    // raw x of the next chunk: word (st, h) of tile t = elements 32st + 8kk + 4h .. +3
+    // raw x of the next chunk: word (st, h) of tile t = elements 32st + 16h + 4kk .. +3
     f4 xr[2][2][2];
     u4 ur[NT];
 #pragma unroll
@@ -515,7 +503,7 @@ __device__ __forceinline__ void compress_split_tile(const LongArgs& a, u4* Us, c
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                xr[t][st][h] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], 32 * st + 8 * kk + 4 * h);
+                xr[t][st][h] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], 32 * st + 16 * h + 4 * kk);
 
     for (int c = 0; c < a.nchunk; ++c) {
         const int cn = c < last ? c + 1 : last;
@@ -525,14 +513,14 @@ __device__ __forceinline__ void compress_split_tile(const LongArgs& a, u4* Us, c
         u4 xh[2][2], xl[2][2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
-            const float* mc = mus + c * LC + 32 * st + 8 * kk;
-            const f4 m0 = *(const f4*)mc, m1 = *(const f4*)(mc + 4);
+            const float* mc = mus + c * LC + 32 * st + 4 * kk;
+            const f4 m0 = *(const f4*)mc, m1 = *(const f4*)(mc + 16);
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 split8(xr[t][st][0] - m0, xr[t][st][1] - m1, xh[t][st], xl[t][st]);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
-                    xr[t][st][h] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 32 * st + 8 * kk + 4 * h);
+                    xr[t][st][h] = load_x4<BF16, FAST>(a, ok[t], s[t], sc[t], cn * LC + 32 * st + 16 * h + 4 * kk);
             }
         }
         const u4* Uc = Us + (c & 1) * CH4;
@@ -632,7 +620,7 @@ __global__ __launch_bounds__(256, 2) void decompress_split_kernel(LongArgs a)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     v[h] = f4{0.f, 0.f, 0.f, 0.f};
-                    const int c0 = 32 * ks + 8 * kk + 4 * h;
+                    const int c0 = 32 * ks + 16 * h + 4 * kk;
                     if (!ok[t] || c0 >= a.k) continue;
                     const float* p = Y + s[t] * a.kfull + a.c0 + c0;
                     if ((a.kfull & 3) == 0) {
@@ -717,11 +705,11 @@ __global__ void pack_long_split_kernel(const float* U, unsigned short* Upc, unsi
         };
         {   // compress: w = (st * 2 + p) * NT + nt
             const int nt = w % NT, p = (w / NT) & 1, st = w / (2 * NT);
-            Upc[(size_t)b * per + i] = term(c * LC + 32 * st + 8 * kk + j, 16 * nt + m, p);
+            Upc[(size_t)b * per + i] = term(c * LC + 32 * st + 16 * (j >> 2) + 4 * kk + (j & 3), 16 * nt + m, p);
         }
         {   // decompress: w = ((et * NKS + ks) * 2 + p)
             const int p = w & 1, ks = (w >> 1) % NKS, et = (w >> 1) / NKS;
-            Upd[(size_t)b * per + i] = term(c * LC + 16 * et + m, 32 * ks + 8 * kk + j, p);
+            Upd[(size_t)b * per + i] = term(c * LC + 16 * et + m, 32 * ks + 16 * (j >> 2) + 4 * kk + (j & 3), p);
         }
     }
 }
@@ -780,12 +768,13 @@ size_t gvq_long_split_pack_halves(int d, int k)
 // Which matrix pipe: exact fp32 products while they keep up with memory (2dk / (4(d + k)) below 10
 // flop per byte; at 14, d = 256 and k = 32, the fp32 decompress already falls a quarter behind the
 // split one), the bf16 split above that.  Option 2 overrides: 1 = always fp32 products, 2 = always
-// the split.
+// the split, with the basis-stationary compress kernel (gvq_codec_ws.hip) wherever it can run, 3 = the
+// split, never that kernel.
 bool gvq_long_split(const gvq_basis* h)
 {
     const int mode = gvq_opt_long_mode();
     if (mode == 1) return false;
-    if (mode == 2) return true;
+    if (mode >= 2) return true;
     const int k = h->k < 128 ? h->k : 128;   // per pass
     return 2.0 * h->d * k / (4.0 * (h->d + k)) >= 10.0;
 }
@@ -802,6 +791,7 @@ int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st)
                            split_nt(h->k), nchunk, 128 * p, np, p);
         GVQ_HIP(hipGetLastError());
     }
+    if (gvq_ws_shape(h)) return gvq_launch_pack_ws(h, st);
     return GVQ_OK;
 }
 
@@ -923,10 +913,21 @@ static int decompress_split_nt(const gvq_basis* h, const LongArgs& a, int NT, hi
 int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,
                              int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
+    const bool split = gvq_long_split(h), bf = h->dtype == GVQ_BF16;
+    // whole 16-slice tiles of fp32 gradients: U in registers, where that is the faster kernel (option 2: 2 = wherever it
+    // can run, 3 = nowhere)
+    const int mode = gvq_opt_long_mode();
+    if (split && !bf && gvq_ws_shape(h) && mode != 3 && (mode == 2 || gvq_ws_pays(h))) {
+        int64_t done = 0;
+        const int rc = gvq_launch_compress_ws(h, grad, n_workers, first_slice, n_slices, comp_in, out, st, &done);
+        if (rc != GVQ_OK) return rc;
+        first_slice += done;
+        n_slices -= done;
+        if (n_slices <= 0) return GVQ_OK;
+    }
     LongArgs a0 = long_args(h, grad, out, h->d_Upc, first_slice, n_slices);
     a0.acc_in = comp_in;
     a0.n_workers = (float)n_workers;
-    const bool split = gvq_long_split(h), bf = h->dtype == GVQ_BF16;
     for (int p = 0; p < gvq_long_passes(h->k); ++p) {
         int rc;
         if (split) {
@@ -958,8 +959,8 @@ int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, fl
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                                void* out, gvq_dtype_t odt, hipStream_t st)
 {
-    const LongArgs a0 = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
     const bool split = gvq_long_split(h), bf = odt == GVQ_BF16;
+    const LongArgs a0 = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
     const unsigned short* Upd_split = h->d_Upb + (size_t)h->B * gvq_long_split_pack_halves(h->d, h->k);
     for (int p = 0; p < gvq_long_passes(h->k); ++p) {
         int rc;

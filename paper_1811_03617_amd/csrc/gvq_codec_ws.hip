@@ -1,0 +1,275 @@
+// Basis-stationary compress kernel for long slices (Section 3, "slice size": d = 768 in the paper's example) on
+// the bf16 matrix pipe: Eq. (2), y = U^T (x - mu/N).
+//
+// The LDS-tiled kernels of gvq_codec_long.hip stream U through LDS once per 128-slice tile and walk over the
+// gradient in 256-byte strips of 128 rows.  Here the roles are swapped.  A compute unit's register files hold
+// 512 KB, more than the two-term bf16 copy of a whole basis (4dk bytes: 288 KB at d = 768, k = 96), so one
+// work-group of 8 waves per compute unit keeps U in registers for the whole launch, an eighth of the slice's
+// elements per wave (all column tiles), and the gradient streams past it in tiles of 16 whole slices, each tile
+// one contiguous run of 64d bytes: the memory system sees a plain sequential stream and U costs no traffic after
+// the first microseconds.  A tile's 16 x d floats are copied global -> LDS by the load unit itself
+// (global_load_lds: no registers in between, up to two tiles in flight while one is worked on); a wave reads its
+// strip in B-operand order, centres and splits it, and accumulates the 16 x k partial products of its strip; the
+// 8 partial results meet in LDS, each in the strip of the tile that its wave alone reads, and are added.
+//
+// Products as in the split kernels: a = a1 + a2 in bf16, x u = x1 u1 + x1 u2 + x2 u1 with fp32 accumulation on
+// v_mfma_f32_16x16x32_bf16.  Shapes: fp32 gradients, one basis, d a multiple of 256, k of 4, and the limits of
+// gvq_ws_shape; whole 16-slice tiles only, the caller sends what is left of a range to the LDS-tiled kernels.
+// The same scheme for Eq. (4) was tried and dropped: its 16 x d output tile leaves the compute unit in one burst
+// per tile, and no arrangement of those stores (direct, through LDS as whole rows, spread over the next tile's
+// products, fewer storing waves) came within 10 % of the LDS-tiled decompress kernels.
+#include "gvq_internal.h"
+
+#include "gvq_device.h"
+
+struct WsArgs {
+    const void* in;          // gradient
+    void* out;               // y
+    const float* acc_in;     // partial sum of the ring step to add, or null
+    const u4* Upack;         // the operand-order copy of U (layout at the pack kernel)
+    const float* mu;         // [d]
+    int64_t first;           // first slice
+    int64_t ntiles;          // 16-slice tiles
+    int d, k;
+    float n_workers;
+};
+
+#define WS_WAVES 8
+#define WS_ROWPAD 4          // floats between LDS rows of the x tile: 16 lanes x 128 bits then cover all banks
+
+// 1 KB, 16 bytes per lane, global -> LDS without passing through registers.  lds_off: wave-uniform
+// byte offset of the first lane's bytes inside the work-group's LDS.  Written as inline assembly so
+// that the compiler does not pair the copy with the LDS reads of the *other* buffer (it would wait
+// for the copy before every such read).
+__device__ __forceinline__ void copy_1k_to_lds(const void* src_lane, unsigned int lds_off)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_off)
+                 : "memory", "m0");
+}
+
+// --------------------------------------------------------------------------------------
+// compress.  LDS: xs[2][16][d + 4] floats, part[8][NT][64] 128-bit words, mus[d] floats.
+// --------------------------------------------------------------------------------------
+template <int STEPS, int NT>
+__global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
+{
+    extern __shared__ f4 smem[];
+    constexpr int D = 256 * STEPS, RS = D + WS_ROWPAD, EW = 32 * STEPS;
+    static_assert(16 * NT <= EW, "a wave's partial result must fit the strip of the tile it alone reads");
+    float* xs = (float*)smem;                 // [nbuf][16][RS]
+    float* mus = xs + nbuf * 16 * RS;         // [D]
+    const int tid = threadIdx.x, lane = tid & 63, n_ = lane & 15, kk = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    u4 us[STEPS][NT][2];
+#pragma unroll
+    for (int st = 0; st < STEPS; ++st)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) us[st][nt][p] = a.Upack[((((size_t)w * STEPS + st) * NT + nt) * 2 + p) * 64 + lane];
+    for (int e = tid; e < D; e += 512) mus[e] = a.mu[e] / a.n_workers;
+
+    const unsigned int xs_off = (unsigned int)(size_t)(__attribute__((address_space(3))) void*)xs;
+    // Piece i (0 .. 2 STEPS - 1) of this wave's share of a tile: 1 KB of row 2w + i / STEPS, into buffer buf
+    auto copy_piece = [&](int64_t tile, int buf, int i) {
+        const int row = 2 * w + i / STEPS, q = i % STEPS;
+        const float* g = (const float*)a.in + ((a.first + 16 * tile + row) * (int64_t)D + q * 256 + lane * 4);
+        copy_1k_to_lds(g, xs_off + 4u * (unsigned int)((buf * 16 + row) * RS + q * 256));
+    };
+
+    // Wave v adds up column tile v when that tile holds a comp below k; it then issues exactly one store per tile.
+    const bool adds = 16 * w < a.k;
+    // nbuf - 1 tiles are in flight while one is worked on
+    const int ahead = nbuf - 1;
+    int64_t t = blockIdx.x;
+    for (int p = 0; p < ahead; ++p) {
+        const int64_t tp = t + (int64_t)p * gridDim.x;
+        if (tp < a.ntiles) {
+#pragma unroll
+            for (int i = 0; i < 2 * STEPS; ++i) copy_piece(tp, p, i);
+        }
+    }
+    drain_memory();   // U and the first tiles have arrived: the loop below inherits no wait
+    for (int buf = 0; t < a.ntiles; t += gridDim.x, buf = buf + 1 == nbuf ? 0 : buf + 1) {
+        // the tile to ask for (the current one again when there is none: the count in flight stays the same)
+        // and the buffer it goes to, which held the tile before this one
+        const int64_t ta = t + (int64_t)ahead * gridDim.x < a.ntiles ? t + (int64_t)ahead * gridDim.x : t;
+        const int bufa = buf == 0 ? nbuf - 1 : buf - 1;
+        // This wave's rows of the current tile: memory operations retire in order, and the requests younger
+        // than them are the copies of the tiles between (2 STEPS each) and one store per tile for the waves
+        // that add up a column tile.
+        if (ahead == 2) {
+            if (adds) wait_vmem_at_most<2 * STEPS + 2>(); else wait_vmem_at_most<2 * STEPS>();
+        } else {
+            if (adds) wait_vmem_at_most<1>(); else wait_vmem_at_most<0>();
+        }
+        __syncthreads();
+        f4 acc[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
+        float* xrow = xs + (buf * 16 + n_) * RS + EW * w + 4 * kk;
+        const float* mrow = mus + EW * w + 4 * kk;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            // lane (n, kk): elements EW w + 32 st + 16 h + 4 kk .. + 3, h = 0, 1, of slice n
+            const f4 x0 = *(const f4*)(xrow + 32 * st), x1 = *(const f4*)(xrow + 32 * st + 16);
+            const f4 m0 = *(const f4*)(mrow + 32 * st), m1 = *(const f4*)(mrow + 32 * st + 16);
+            // two pieces of the tile ahead per step, between the products: every wave is past the second
+            // barrier of the tile that used that buffer
+            copy_piece(ta, bufa, 2 * st);
+            copy_piece(ta, bufa, 2 * st + 1);
+            u4 xh, xl;
+            split8(x0 - m0, x1 - m1, xh, xl);
+            const lbf8 bh = __builtin_bit_cast(lbf8, xh), bl = __builtin_bit_cast(lbf8, xl);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bl, acc[nt], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][1]), bh, acc[nt], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bh, acc[nt], 0, 0, 0);
+        }
+        // The partial result goes where this wave's strip of x was: nobody else reads that strip, and this wave
+        // is done with it.  Register r of lane (n, kk) of column tile nt: row n, float EW w + 16 nt + 4 kk + r.
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) *(f4*)(xrow + 16 * nt) = acc[nt];
+        __syncthreads();
+        // wave v adds the 8 partial results of column tile v (comps 16 v + 4 kk + r of slice n).  The
+        // buffer is next written by the copy of a later tile, which every wave asks for after the next barrier.
+        if (adds) {
+            const float* prow = xs + (buf * 16 + n_) * RS + 16 * w + 4 * kk;
+            f4 s = *(const f4*)prow;
+#pragma unroll
+            for (int v = 1; v < WS_WAVES; ++v) s += *(const f4*)(prow + EW * v);
+            const int c0 = 16 * w + 4 * kk;
+            const int64_t o = (a.first + 16 * t + n_) * a.k + c0;
+            float* Y = (float*)a.out;
+            if (c0 < a.k) {   // k is a multiple of 4; true for the lanes kk = 0 at least
+                if (a.acc_in) s += *(const f4*)(a.acc_in + o);
+                *(f4*)(Y + o) = s;
+            }
+        }
+    }
+    drain_memory();   // the last copies have no reader: let them land before the work-group's LDS is released
+}
+
+// --------------------------------------------------------------------------------------
+// The operand-order copy of U, 8 bf16 per 128-bit word, term p = 0: bf16(U), p = 1: bf16(U - term 0); zero where
+// comp >= k.  Uc[w][st][nt][p][lane (m, kk)][j] = U[EW w + 32 st + r(kk, j)][16 nt + m], EW = d/8,
+// r(kk, j) = 16 (j / 4) + 4 kk + j % 4 (the order in which a lane reads its strip of x).
+// --------------------------------------------------------------------------------------
+__global__ void pack_ws_kernel(const float* U, unsigned short* Uc, int d, int k, int NT)
+{
+    const int EW = d / 8, STEPS = d / 256;
+    const size_t n = (size_t)WS_WAVES * STEPS * NT * 2 * 512;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += (size_t)gridDim.x * blockDim.x) {
+        const int j = (int)(q & 7), lane = (int)((q >> 3) & 63), m = lane & 15, kk = lane >> 4, p = (int)((q >> 9) & 1);
+        size_t g = q >> 10;
+        const int nt = (int)(g % NT); g /= NT;
+        const int st = (int)(g % STEPS), w = (int)(g / STEPS);
+        const int e = EW * w + 32 * st + 16 * (j >> 2) + 4 * kk + (j & 3), comp = 16 * nt + m;
+        unsigned short v = 0;
+        if (comp < k) {
+            const float u = U[(size_t)e * k + comp];
+            const unsigned int t0 = f32_to_bf16_rne(u);
+            v = (unsigned short)(p == 0 ? t0 : f32_to_bf16_rne(u - __uint_as_float(t0 << 16)));
+        }
+        Uc[q] = v;
+    }
+}
+
+// ======================================================================================
+// host side
+// ======================================================================================
+static int ws_nt(int k) { const int nt = (k + 15) / 16; return nt + (nt & 1); }   // column tiles, even
+
+// LDS: nbuf tiles of 16 padded rows, and mu
+static size_t ws_lds(int d, int nbuf) { return sizeof(float) * ((size_t)nbuf * 16 * (d + WS_ROWPAD) + d); }
+// Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two
+static int ws_nbuf(int d) { return ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
+
+// One basis, d in {256, 512, 768, 1024}, k a multiple of 4, U fits the registers of 8 waves (d/256 x NT words of
+// 8 registers, at most 18), and a wave's partial result fits its strip of the tile (16 floats per column tile,
+// d/8 per strip).
+bool gvq_ws_shape(const gvq_basis* h)
+{
+    if (h->B != 1 || h->d % 256 != 0 || h->d > 1024 || h->k % 4 != 0) return false;
+    return (h->d / 256) * ws_nt(h->k) <= 18 && 16 * ws_nt(h->k) <= h->d / 8;
+}
+
+// Where it beats the LDS-tiled split kernel on 138 M elements: d = 256 (5.1 against 4.7 TB/s at k = 32), d = 1024
+// (3.9 against 3.2 at k = 64), d = 768 from 3 column tiles up (3.9 against 3.6 at k = 96); level or 1 - 3 % behind
+// at d = 512 and at d = 768, k <= 32.
+bool gvq_ws_pays(const gvq_basis* h) { return h->d == 256 || h->d == 1024 || (h->d == 768 && h->k > 32); }
+
+// bf16 values of the operand-order copy
+size_t gvq_ws_pack_halves(int d, int k) { return (size_t)WS_WAVES * (d / 256) * ws_nt(k) * 2 * 512; }
+
+int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st)
+{
+    hipLaunchKernelGGL(pack_ws_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws, h->d, h->k, ws_nt(h->k));
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+// Whole 16-slice tiles at the start of [first_slice, first_slice + n_slices) that lie inside the gradient.
+static int64_t ws_tiles(const gvq_basis* h, int64_t first_slice, int64_t n_slices)
+{
+    const int64_t full = h->M / h->d;
+    const int64_t end = first_slice + n_slices < full ? first_slice + n_slices : full;
+    return end > first_slice ? (end - first_slice) / 16 : 0;
+}
+
+template <auto KERN>
+static int launch_ws(const gvq_basis* h, const WsArgs& a, size_t lds, int nbuf, hipStream_t st)
+{
+    static size_t allowed = 0;   // per kernel: the largest dynamic LDS size asked for so far
+    if (lds > allowed) {
+        GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        allowed = lds;
+    }
+    const int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
+    hipLaunchKernelGGL(KERN, dim3((unsigned)grid), dim3(512), lds, st, a, nbuf);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+template <int STEPS>
+static int compress_ws_nt(const gvq_basis* h, const WsArgs& a, hipStream_t st)
+{
+    const int NT = ws_nt(h->k), nbuf = ws_nbuf(256 * STEPS);
+    const size_t lds = ws_lds(256 * STEPS, nbuf);
+    // the shapes gvq_ws_shape lets through: 16 NT <= 32 STEPS, and STEPS x NT <= 18
+    if constexpr (STEPS == 4) {
+        if (NT == 4) return launch_ws<compress_ws_kernel<4, 4>>(h, a, lds, nbuf, st);
+    }
+    if constexpr (STEPS == 3) {
+        if (NT == 6) return launch_ws<compress_ws_kernel<3, 6>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<3, 4>>(h, a, lds, nbuf, st);
+    }
+    if constexpr (STEPS == 2) {
+        if (NT == 4) return launch_ws<compress_ws_kernel<2, 4>>(h, a, lds, nbuf, st);
+    }
+    return launch_ws<compress_ws_kernel<STEPS, 2>>(h, a, lds, nbuf, st);
+}
+
+// Compresses the whole tiles at the start of the range; *done = the slices it took.
+int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
+                           const float* comp_in, float* out, hipStream_t st, int64_t* done)
+{
+    WsArgs a;
+    a.in = grad; a.out = out; a.acc_in = comp_in; a.Upack = (const u4*)h->d_Uws; a.mu = h->d_mu;
+    a.first = first_slice; a.ntiles = ws_tiles(h, first_slice, n_slices); a.d = h->d; a.k = h->k;
+    a.n_workers = (float)n_workers;
+    *done = 16 * a.ntiles;
+    if (a.ntiles == 0) return GVQ_OK;
+    switch (h->d / 256) {
+    case 1: return compress_ws_nt<1>(h, a, st);
+    case 2: return compress_ws_nt<2>(h, a, st);
+    case 3: return compress_ws_nt<3>(h, a, st);
+    default: return compress_ws_nt<4>(h, a, st);
+    }
+}

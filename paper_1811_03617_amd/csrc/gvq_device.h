@@ -80,6 +80,20 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float a, float b)
     return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, gvq_bf2));
 }
 
+typedef __bf16 lbf8 __attribute__((ext_vector_type(8)));
+
+// 8 floats -> their two bf16 terms, packed in operand order (element 2i in the low half of word i)
+__device__ __forceinline__ void split8(const f4& v0, const f4& v1, u4& hi, u4& lo)
+{
+    float r[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned int h = pack_bf16x2(r[2 * i], r[2 * i + 1]);
+        hi[i] = h;
+        lo[i] = pack_bf16x2(r[2 * i] - __uint_as_float(h << 16), r[2 * i + 1] - __uint_as_float(h & 0xffff0000u));
+    }
+}
+
 // Orders this wave's LDS traffic for the compiler: what one lane wrote is read by another
 // lane of the same wave afterwards.  The hardware executes a wave's LDS instructions in
 // order, so no s_barrier is needed; this only stops the compiler from moving LDS accesses

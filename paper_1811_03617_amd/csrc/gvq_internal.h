@@ -38,6 +38,8 @@ struct gvq_basis {
     float* d_Upd = nullptr;     // [B][d][KP] U in decompress-MFMA operand order
     unsigned short* d_Upb = nullptr;  // [B][d/32][3][NT][64][8] bf16 three-term split of U (bf16 gradients);
                                       // long slices: the two-term copies, compress order then decompress order
+    unsigned short* d_Uws = nullptr;  // basis-stationary compress kernel (gvq_ws_shape): two-term bf16 copy of U in its
+                                      // operand order, per wave
     float* d_Umu = nullptr;     // [B][KP] U^T mu (bf16 gradients)
     double* d_eig = nullptr;    // [B][d]
     double* d_cov = nullptr;    // [B][d][d]
@@ -82,7 +84,8 @@ int gvq_hip_fail(hipError_t e, const char* what);
 int gvq_opt_wg_per_cu();
 // Tiles per run in the MFMA kernels' schedule (0 = default).
 int gvq_opt_run_tiles();
-// LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split.
+// LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split, with the
+// basis-stationary compress kernel wherever it can run, 3 = the bf16 split without that kernel.
 int gvq_opt_long_mode();
 // Bit mask: send every tile through the bounds-checked general phase (1: fp32-pipe compress, 2: bf16-pipe
 // compress, 4: decompress).
@@ -125,6 +128,14 @@ int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers
 int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, float* loss_slice, hipStream_t st);
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                                void* out, gvq_dtype_t odt, hipStream_t st);
+// Basis-stationary compress kernel (gvq_codec_ws.hip): U stays in registers, the gradient streams past in tiles
+// of 16 whole slices.  The launcher takes the whole tiles at the start of the range and reports the slices done.
+bool gvq_ws_shape(const gvq_basis* h);   // it can take this handle's shape
+bool gvq_ws_pays(const gvq_basis* h);    // ... and is the faster one there
+size_t gvq_ws_pack_halves(int d, int k);   // bf16 values of its operand-order copy of U
+int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st);
+int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
+                           const float* comp_in, float* out, hipStream_t st, int64_t* done);
 int gvq_large_groups(int d);
 size_t gvq_large_partial_doubles(int d, int chunks);   // per basis
 int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipStream_t st);

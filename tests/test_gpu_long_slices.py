@@ -191,6 +191,12 @@ def _check_codec(w, out_dtype=None):
                  REL_TOL, "decompress")
     assert_close(out.cpu().numpy(), oracle.decompress(ref_total, U64, mu64, w.M, offsets=offs), REL_TOL,
                  "end to end")
+    if out_dtype == "bf16":   # the same reconstruction rounded to bf16: half a unit in the last of 8 bits
+        out16 = torch.full((w.M,), float("nan"), device=DEV, dtype=torch.bfloat16)
+        b.decompress(total, out16, "bf16")
+        ref_x = oracle.decompress(got_total.astype(np.float64), U64, mu64, w.M, offsets=offs)
+        got16 = out16.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got16 - ref_x) <= 2.0 ** -8 * np.abs(ref_x) + REL_TOL * np.max(np.abs(ref_x)))
     ref_loss = oracle.local_loss(workers_np[0], U64, mu64, w.N, dtype=w.dtype, offsets=offs)
     energy = oracle.local_loss(workers_np[0], np.zeros((w.n_blocks, w.d, 1)), mu64, w.N, dtype=w.dtype, offsets=offs)
     got_loss = loss.cpu().numpy()
@@ -212,7 +218,7 @@ def _check_codec(w, out_dtype=None):
     (256 * 260 + 5, 256, 131, 2, "bf16", 0),         # second pass of 3 comps, k not a multiple of 4
     (1024 * 70 + 9, 1024, 520, 2, "f32", 0),         # five passes, the last of 8 comps
 ])
-@pytest.mark.parametrize("pipe", [1, 2], ids=["fp32-products", "bf16-split-products"])
+@pytest.mark.parametrize("pipe", [1, 2, 3], ids=["fp32-products", "bf16-split-products", "bf16-split-lds-tiled-only"])
 def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
     assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
     try:
@@ -221,8 +227,30 @@ def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
         gvq.lib().gvq_set_option(2, 0)
 
 
+@pytest.mark.parametrize("M,d,k,N", [
+    (512 * 200 + 77, 512, 64, 2),
+    (1024 * 60 + 5, 1024, 32, 2),
+    (768 * 150, 768, 40, 2),        # comps end inside a 32-comp step
+    (256 * 500 + 3, 256, 32, 2),    # the smallest slice it takes
+    (256 * 300, 256, 128, 2),       # too many column tiles for a wave's strip: the LDS-tiled kernels
+    (512 * 100, 512, 52, 3),
+    (768 * 20 + 5, 768, 96, 2),     # one 16-slice tile, the rest to the LDS-tiled kernels
+    (768 * 10, 768, 96, 2),         # no whole tile
+    (768 * 4113 + 700, 768, 96, 2), # more tiles than work-groups, several per work-group
+])
+def test_basis_stationary_kernels(M, d, k, N):
+    """fp32 gradients, one basis, d a multiple of 256, the bf16-split pipe by default: compress keeps U in
+    registers and the gradient streams past in 16-slice tiles; compared with the oracle like every other route."""
+    for pipe in (0, 2):   # where it is the default, and wherever it can run
+        assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
+        try:
+            _check_codec(_wl(M, d, k, N, 2), out_dtype="bf16")
+        finally:
+            gvq.lib().gvq_set_option(2, 0)
+
+
 def test_pipe_option_range():
-    assert gvq.lib().gvq_set_option(2, 3) == gvq.EINVAL
+    assert gvq.lib().gvq_set_option(2, 4) == gvq.EINVAL
     assert gvq.lib().gvq_set_option(2, 0) == gvq.OK
 
 

@@ -31,6 +31,8 @@ CASES = [
     (192 * 300 + 5, 192, 7, "f32", 192 * 100),
     # more than 128 comps per slice: one pass of the long-slice kernels per 128 columns
     (512 * 200 + 9, 512, 200, "f32", 0), (256 * 300 + 5, 256, 130, "bf16", 256 * 100),
+    # the paper's slice length, one basis: whole 16-slice tiles of a segment go to the basis-stationary compress kernel
+    (768 * 100 + 9, 768, 96, "f32", 0),
 ]
 
 
@@ -39,7 +41,7 @@ def test_segment_calls_match_the_oracle_and_touch_nothing_else(M, d, k, dtype, b
     if d <= 128:
         _check_segments(M, d, k, dtype, block_elems)
         return
-    for pipe in (1, 2):   # long slices: fp32 products, then products of bf16 splits
+    for pipe in (1, 2, 3):   # long slices: fp32 products, products of bf16 splits, those without the basis-stationary kernel
         assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
         try:
             _check_segments(M, d, k, dtype, block_elems)
