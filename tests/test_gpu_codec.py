@@ -220,3 +220,28 @@ def test_codec_is_bitwise_reproducible():
     for x, y in zip(a[0], b[0]):
         assert np.array_equal(x, y)
     assert np.array_equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+@pytest.mark.parametrize("M,d,k,N,dtype,block_elems", [
+    (128 * 5000 + 40, 128, 32, 3, "f32", 0),
+    (128 * 5000 + 40, 128, 16, 2, "bf16", 128 * 700),    # several bases: super-tiles from the handle's plan
+    (64 * 9000 + 6, 64, 16, 2, "bf16", 0),
+    (32 * 20000 + 8, 32, 8, 2, "f32", 32 * 3000),
+    (16 * 30000 + 3, 16, 4, 2, "f32", 0),
+])
+def test_both_loops_of_the_register_resident_kernels_agree_bit_for_bit(M, d, k, N, dtype, block_elems):
+    """These kernels run whole tiles of one basis through a branch-free loop and the rest through a
+    bounds-checked one; option 3 sends everything through the latter.  Same arithmetic in the same order:
+    the results must be identical, and the default run is compared with the oracle by the tests above."""
+    w = _wl(M, d, k, N, dtype=dtype, block_elems=block_elems)
+    U32, mu32 = _oracle_basis(w)
+    dev = [g.to(DEV) for g in synth.worker_gradients(w, "cpu")]
+    a = _run_codec(w, U32, mu32, dev)
+    assert gvq.lib().gvq_set_option(3, 7) == gvq.OK
+    try:
+        b = _run_codec(w, U32, mu32, dev)
+    finally:
+        assert gvq.lib().gvq_set_option(3, 0) == gvq.OK
+    for x, y in zip(a[0], b[0]):
+        assert np.array_equal(x, y)
+    assert np.array_equal(a[1], b[1]) and torch.equal(a[2], b[2])
