@@ -149,15 +149,38 @@ __device__ __forceinline__ int bj_global(int nb, int I, int J, int x)
     return x < nb ? I * nb + x : J * nb + (x - nb);
 }
 
-// Rotation (c, s) that annihilates a_pq: t = tan, the smaller root of t^2 + 2 t theta - 1 = 0 with
-// theta = (a_qq - a_pp) / (2 a_pq), written without the division by a_pq:
-// t = 2 a_pq sgn(dd) / (|dd| + sqrt(dd^2 + 4 a_pq^2)), dd = a_qq - a_pp;  c = 1 / sqrt(1 + t^2), s = t c.
+// 1 / sqrt(x) in full double precision for x in the range where x and 1/x are normal numbers: the
+// hardware's approximation (v_rsq_f64) and two Newton steps.
+__device__ __forceinline__ double bj_rsqrt(double x)
+{
+    double y = __builtin_amdgcn_rsq(x);
+    const double h = 0.5 * x;
+    y = y * (1.5 - h * y * y);
+    y = y * (1.5 - h * y * y);
+    return y;
+}
+
+// Rotation (c, s) that annihilates a_pq: tan of the angle is the smaller root of t^2 + 2 t theta - 1 = 0,
+// theta = (a_qq - a_pp) / (2 a_pq).  With dd = a_qq - a_pp and h = sqrt(dd^2 + 4 a_pq^2):
+//     c^2 = (1 + |dd| / h) / 2,   s = sgn(dd) a_pq / (h c)        (dd = 0 counts as positive),
+// which needs two reciprocal square roots and no division: this runs on 32 lanes between two barriers of
+// every inner round, with the whole work-group waiting for it.  Outside the range where dd^2 + 4 a_pq^2
+// is safely a normal number the textbook form with its divisions is used.
 __device__ __forceinline__ void bj_rotation(double app, double aqq, double apq, double& c, double& s)
 {
     c = 1.0; s = 0.0;
     if (apq == 0.0) return;
     const double dd = aqq - app;
-    const double r = sqrt(dd * dd + 4.0 * apq * apq);
+    const double x = dd * dd + 4.0 * apq * apq;
+    if (x > 1e-280 && x < 1e280) {
+        const double rh = bj_rsqrt(x);
+        const double c2 = 0.5 + 0.5 * fabs(dd) * rh;
+        const double rc = bj_rsqrt(c2);
+        c = c2 * rc;
+        s = (dd >= 0.0 ? apq : -apq) * rh * rc;
+        return;
+    }
+    const double r = hypot(dd, 2.0 * apq);
     const double t = (dd >= 0.0 ? 2.0 : -2.0) * apq / (fabs(dd) + r);
     c = 1.0 / sqrt(1.0 + t * t);
     s = t * c;
@@ -213,34 +236,56 @@ __device__ __forceinline__ void bj_solve_pair(const BjArgs& a, double* smem, dou
     };
     if (tid < half) params(0);
     __syncthreads();
+    // Thread layout of a round: rotation j = tid % 32 on the column side for every thread (its parameters are read
+    // once per round), rotations i = tid / 32 + 8 u on the row side of S (four 2 x 2 blocks per thread), rows
+    // (tid - 64) / 32 + 6 v of Q for the three waves that update it.  All loops unrolled: the LDS reads of a
+    // thread's blocks are in flight together instead of one round trip after the other.
+    const int j = tid & (half - 1), i0 = tid >> 5, qrow0 = (tid - 64) >> 5;
     for (int t = 0; t < rounds; ++t) {
         const int o = (t & 1) * half;
+        const int r = pp[o + j], u = qq[o + j];
+        const double cj = cs[o + j], sj = sn[o + j];
         // S <- J^T S J: one 2 x 2 block per (rotation i, rotation j), in place (a block reads only itself)
+        int p4[4], q4[4];
+        double ci4[4], si4[4], apr[4], apu[4], aqr[4], aqu[4];
 #pragma unroll
-        for (int u4 = 0; u4 < half * half / 256; ++u4) {
-            const int idx = tid + 256 * u4, i = idx / half, j = idx % half;
-            const int p = pp[o + i], q = qq[o + i], r = pp[o + j], u = qq[o + j];
-            const double ci = cs[o + i], si = sn[o + i], cj = cs[o + j], sj = sn[o + j];
-            const double apr = S[p * m + r], apu = S[p * m + u], aqr = S[q * m + r], aqu = S[q * m + u];
-            const double xpr = ci * apr - si * aqr, xpu = ci * apu - si * aqu;
-            const double xqr = si * apr + ci * aqr, xqu = si * apu + ci * aqu;
+        for (int v = 0; v < 4; ++v) {
+            const int i = i0 + 8 * v;
+            p4[v] = pp[o + i]; q4[v] = qq[o + i]; ci4[v] = cs[o + i]; si4[v] = sn[o + i];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            apr[v] = S[p4[v] * m + r]; apu[v] = S[p4[v] * m + u];
+            aqr[v] = S[q4[v] * m + r]; aqu[v] = S[q4[v] * m + u];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const double ci = ci4[v], si = si4[v];
+            const double xpr = ci * apr[v] - si * aqr[v], xpu = ci * apu[v] - si * aqu[v];
+            const double xqr = si * apr[v] + ci * aqr[v], xqu = si * apu[v] + ci * aqu[v];
             double ypr = cj * xpr - sj * xpu, ypu = sj * xpr + cj * xpu;
             double yqr = cj * xqr - sj * xqu, yqu = sj * xqr + cj * xqu;
-            if (i == j) { ypu = 0.0; yqr = 0.0; }
-            S[p * m + r] = ypr; S[p * m + u] = ypu; S[q * m + r] = yqr; S[q * m + u] = yqu;
+            if (i0 + 8 * v == j) { ypu = 0.0; yqr = 0.0; }
+            S[p4[v] * m + r] = ypr; S[p4[v] * m + u] = ypu; S[q4[v] * m + r] = yqr; S[q4[v] * m + u] = yqu;
         }
         __syncthreads();
         if (tid < 64) {
             if (tid < half && t + 1 < rounds) params(t + 1);
         } else {
-            // Q <- Q J
-            for (int idx = tid - 64; idx < m * half; idx += 192) {
-                const int row = idx / half, j = idx % half;
-                const int r = pp[o + j], u = qq[o + j];
-                const double cj = cs[o + j], sj = sn[o + j];
-                const double vr = Q[row * m + r], vu = Q[row * m + u];
-                Q[row * m + r] = cj * vr - sj * vu;
-                Q[row * m + u] = sj * vr + cj * vu;
+            // Q <- Q J, columns r and u of rows qrow0 + 6 v
+            double vr[11], vu[11];
+#pragma unroll
+            for (int v = 0; v < 11; ++v) {
+                const int row = qrow0 + 6 * v;
+                if (row < m) { vr[v] = Q[row * m + r]; vu[v] = Q[row * m + u]; }
+            }
+#pragma unroll
+            for (int v = 0; v < 11; ++v) {
+                const int row = qrow0 + 6 * v;
+                if (row < m) {
+                    Q[row * m + r] = cj * vr[v] - sj * vu[v];
+                    Q[row * m + u] = sj * vr[v] + cj * vu[v];
+                }
             }
         }
         __syncthreads();
