@@ -834,7 +834,7 @@ static LongArgs pass_args(const gvq_basis* h, const LongArgs& a0, const void* up
 }
 
 template <auto KERN>
-static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
+static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st, int most = 0)
 {
     const size_t lds = sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * (size_t)a.nchunk * LC;
     static bool attr_set = false;
@@ -855,7 +855,7 @@ static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_
             known_per_cu = occ < 1 ? 1 : occ;
             known_lds = lds;
         }
-        per_cu = known_per_cu;
+        per_cu = most > 0 && known_per_cu > most ? most : known_per_cu;
     }
     const int64_t tiles = a.t1 - a.t0, cap = (int64_t)h->num_cu * per_cu;
     const int grid = (int)(tiles < cap ? tiles : cap);
@@ -876,15 +876,22 @@ static int compress_long_nt(const gvq_basis* h, const LongArgs& a, int NT, hipSt
     }
 }
 
+// Work-groups per compute unit of the decompress kernels, at most.  Their waves spend half their time getting
+// stores accepted, and more work-groups storing at once make that worse: on 138 M elements two per compute unit
+// give 4.95 TB/s at d = 256, k = 32 where the four that fit give 4.35 (d = 512, k = 64: 4.5 against 4.1); with
+// six or more column tiles the matrix work needs a third (d = 768, k = 96: 3.85 against 3.65 with two), and so
+// does bf16 output.
+static int decompress_most(int NT, bool out_bf16) { return NT >= 6 || out_bf16 ? 3 : 2; }
+
 template <bool BF16>
 static int decompress_long_nt(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
 {
     switch (NT) {
-    case 1: return launch_long<decompress_long_kernel<1, BF16>>(h, a, 1, st);
-    case 2: return launch_long<decompress_long_kernel<2, BF16>>(h, a, 2, st);
-    case 4: return launch_long<decompress_long_kernel<4, BF16>>(h, a, 4, st);
-    case 6: return launch_long<decompress_long_kernel<6, BF16>>(h, a, 6, st);
-    default: return launch_long<decompress_long_kernel<8, BF16>>(h, a, 8, st);
+    case 1: return launch_long<decompress_long_kernel<1, BF16>>(h, a, 1, st, decompress_most(1, BF16));
+    case 2: return launch_long<decompress_long_kernel<2, BF16>>(h, a, 2, st, decompress_most(2, BF16));
+    case 4: return launch_long<decompress_long_kernel<4, BF16>>(h, a, 4, st, decompress_most(4, BF16));
+    case 6: return launch_long<decompress_long_kernel<6, BF16>>(h, a, 6, st, decompress_most(6, BF16));
+    default: return launch_long<decompress_long_kernel<8, BF16>>(h, a, 8, st, decompress_most(8, BF16));
     }
 }
 
@@ -903,10 +910,10 @@ template <bool BF16>
 static int decompress_split_nt(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st)
 {
     switch (NT) {
-    case 2: return launch_long<decompress_split_kernel<2, BF16>>(h, a, 2, st);
-    case 4: return launch_long<decompress_split_kernel<4, BF16>>(h, a, 4, st);
-    case 6: return launch_long<decompress_split_kernel<6, BF16>>(h, a, 6, st);
-    default: return launch_long<decompress_split_kernel<8, BF16>>(h, a, 8, st);
+    case 2: return launch_long<decompress_split_kernel<2, BF16>>(h, a, 2, st, decompress_most(2, BF16));
+    case 4: return launch_long<decompress_split_kernel<4, BF16>>(h, a, 4, st, decompress_most(4, BF16));
+    case 6: return launch_long<decompress_split_kernel<6, BF16>>(h, a, 6, st, decompress_most(6, BF16));
+    default: return launch_long<decompress_split_kernel<8, BF16>>(h, a, 8, st, decompress_most(8, BF16));
     }
 }
 
