@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--skip-fit", action="store_true",
                     help="import a seeded random orthonormal basis instead of fitting one (counter runs: the "
                          "long-slice fit enqueues tens of thousands of small kernels)")
+    ap.add_argument("--option", action="append", default=[], metavar="INDEX=VALUE",
+                    help="gvq_set_option(INDEX, VALUE) before the run (launch tuning, for A/B timings); repeatable")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (the N workers are simulated as N "
@@ -45,11 +47,14 @@ def main():
 
     import torch
 
-    from paper_1811_03617_amd import WORKLOADS
+    from paper_1811_03617_amd import WORKLOADS, gvq
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    for o in args.option:
+        index, value = (int(v) for v in o.split("="))
+        gvq.gvq_set_option(index, value)
     # "all": one JSON line per workload (the table of the design doc from one command); the default is the
     # headline workload alone, ONE line
     names = list(WORKLOADS) if args.workload == "all" else [args.workload]

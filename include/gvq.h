@@ -262,7 +262,10 @@ const char* gvq_strerror(int status);
  *             compress, 4: decompress); results are identical, for A/B timing;
  *   option 4: pacing of the branch-free loop, -1 = each kernel's default: bit 0 = a wave waits for all its
  *             memory work before it parks the next tile, bit 1 = also after a tile's matrix products,
- *             bit 2 = the matrix products wait for the next tile's loads one by one.
+ *             bit 2 = the matrix products wait for the next tile's loads one by one;
+ *   option 5: with one basis, the number of consecutive super-tiles (2048 elements each) of the branch-free
+ *             loop whose 1 KB rows interleave, so that the waves running side by side sweep one compact
+ *             window of memory row by row; 1 = none, at most 4096; results are identical.
  * The options are plain process-wide variables read at launch time: set them while no other thread is
  * inside a libgvq call.  Returns GVQ_EINVAL for unknown options or values out of range.
  */

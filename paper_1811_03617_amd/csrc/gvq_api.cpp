@@ -16,6 +16,7 @@ static int g_run_tiles = 0;
 static int g_long_mode = 0;
 static int g_no_fast = 0;
 static int g_pace = -1;
+static int g_interleave = 0;
 
 int gvq_hip_fail(hipError_t e, const char* what)
 {
@@ -29,6 +30,7 @@ int gvq_opt_run_tiles() { return g_run_tiles; }
 int gvq_opt_long_mode() { return g_long_mode; }
 int gvq_opt_no_fast() { return g_no_fast; }
 int gvq_opt_pace() { return g_pace; }
+int gvq_opt_interleave() { return g_interleave; }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -59,6 +61,7 @@ int gvq_set_option(int option, int value)
     if (option == 2 && value >= 0 && value <= 3) { g_long_mode = value; return GVQ_OK; }
     if (option == 3 && value >= 0 && value <= 7) { g_no_fast = value; return GVQ_OK; }
     if (option == 4 && value >= -1 && value <= 7) { g_pace = value; return GVQ_OK; }
+    if (option == 5 && value >= 0 && value <= 4096) { g_interleave = value; return GVQ_OK; }
     return GVQ_EINVAL;
 }
 

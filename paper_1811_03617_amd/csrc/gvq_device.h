@@ -42,6 +42,10 @@ struct CodecArgs {
     const int64_t* rest_list; // many bases: [n_rest] the rest tiles
     int64_t n_rest;
     int rest_run;             // rest tiles per run, see RestIter
+    int il;                   // fast phase, one basis: il consecutive super-tiles interleave their 1 KB rows (row r of
+                              // super-tile p of a group is row r il + p % il of the group's il times as many rows), so that
+                              // consecutive waves, which take consecutive super-tiles, read and write one compact window of
+                              // memory at any moment; 1 = none (a super-tile is 2048 consecutive elements).  Whole groups only.
     int pace;                 // fast phase: bit 0 = wait for all memory work before a super-tile is parked,
                               // bit 1 = also after its matrix products (fewer requests in flight per wave), bit 2 = the matrix
                               // products of a super-tile wait for the next one's loads one by one

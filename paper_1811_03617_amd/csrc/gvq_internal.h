@@ -92,6 +92,8 @@ int gvq_opt_long_mode();
 int gvq_opt_no_fast();
 // Pacing of the fast phase (CodecArgs::pace), -1 = each kernel's default.
 int gvq_opt_pace();
+// Super-tiles whose 1 KB rows interleave in the fast phase (CodecArgs::il), 0 = each kernel's default, 1 = none.
+int gvq_opt_interleave();
 
 // Kernel launchers (each only enqueues on `st`; returns GVQ_OK or GVQ_EHIP).
 int gvq_launch_compress(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice,

@@ -36,6 +36,9 @@ def test_strerror_and_option_checks():
     assert gvq.strerror(-99) == "unknown status"
     assert gvq.lib().gvq_set_option(99, 1) == gvq.EINVAL
     assert gvq.lib().gvq_set_option(0, 0) == gvq.OK
+    assert gvq.lib().gvq_set_option(5, 4097) == gvq.EINVAL
+    assert gvq.lib().gvq_set_option(5, -1) == gvq.EINVAL
+    assert gvq.lib().gvq_set_option(5, 0) == gvq.OK
 
 
 @pytest.mark.parametrize("M,d,k,nb,offs", [

@@ -211,6 +211,61 @@ def test_error_paths_on_the_device():
     b.close()
 
 
+def _run_ring(w, U32, mu32, workers_dev, first, count, out_dtype):
+    """Eq. 3 as a ring of fused compress steps over slices [first, first + count), then Eq. 4 on the same range."""
+    b = gvq.Basis(w.M, w.d, w.k, w.block_offsets(), w.dtype)
+    b.import_(U32, mu32)
+    acc = [torch.full((b.S * w.k,), float("nan"), device=DEV) for _ in range(2)]
+    for n, g in enumerate(workers_dev):
+        b.compress_segment(g, len(workers_dev), first, count, acc[(n + 1) % 2] if n else None, acc[n % 2])
+    total = acc[(len(workers_dev) - 1) % 2]
+    out = torch.full((w.M,), float("nan"), device=DEV,
+                     dtype=torch.bfloat16 if out_dtype == "bf16" else torch.float32)
+    b.decompress_segment(total, first, count, out, out_dtype)
+    torch.cuda.synchronize()
+    res = total.cpu().numpy(), out
+    b.close()
+    return res
+
+
+@pytest.mark.parametrize("M,d,k,N,dtype,out_dtype", [
+    (128 * 5000 + 40, 128, 32, 3, "f32", "f32"),
+    (128 * 5000 + 40, 128, 16, 2, "f32", "bf16"),
+    (128 * 5000 + 40, 128, 32, 2, "bf16", "bf16"),
+    (64 * 9000 + 6, 64, 16, 2, "f32", "f32"),
+    (32 * 20000 + 8, 32, 8, 2, "f32", "f32"),
+    (16 * 30000 + 3, 16, 4, 2, "f32", "bf16"),
+])
+def test_row_interleave_of_the_register_resident_kernels_changes_no_bit(M, d, k, N, dtype, out_dtype):
+    """With one basis, groups of super-tiles exchange their 1 KB rows (option 5: the group size; the groups that do
+    not fill up stay as they are).  Which wave computes a slice changes, what it computes does not: every width
+    gives the bits of width 1, on the whole gradient and on a ring segment that starts and ends inside a tile."""
+    w = _wl(M, d, k, N, dtype=dtype)
+    U32, mu32 = _oracle_basis(w)
+    dev = [g.to(DEV) for g in synth.worker_gradients(w, "cpu")]
+    S = (M + d - 1) // d
+    first, count = S // 7 + 3, S // 2 + 5
+
+    def both():
+        return _run_codec(w, U32, mu32, dev, out_dtype), _run_ring(w, U32, mu32, dev, first, count, out_dtype)
+
+    assert gvq.lib().gvq_set_option(5, 1) == gvq.OK
+    try:
+        a, ar = both()
+        for width in (0, 2, 3, 7, 16, 64):
+            assert gvq.lib().gvq_set_option(5, width) == gvq.OK
+            b, br = both()
+            for x, y in zip(a[0], b[0]):
+                assert np.array_equal(x, y), width
+            assert np.array_equal(a[1], b[1]) and torch.equal(a[2], b[2]), width
+            lo, hi = first * k, (first + count) * k
+            assert np.array_equal(ar[0][lo:hi], br[0][lo:hi]), width
+            e0, e1 = first * d, min((first + count) * d, M)
+            assert torch.equal(ar[1][e0:e1], br[1][e0:e1]), width
+    finally:
+        assert gvq.lib().gvq_set_option(5, 0) == gvq.OK
+
+
 def test_codec_is_bitwise_reproducible():
     w = _wl(128 * 2000 + 40, 128, 32, 3)
     U32, mu32 = _oracle_basis(w)
