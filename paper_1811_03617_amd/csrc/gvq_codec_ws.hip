@@ -14,11 +14,15 @@
 //
 // Products as in the split kernels: a = a1 + a2 in bf16, x u = x1 u1 + x1 u2 + x2 u1 with fp32 accumulation on
 // v_mfma_f32_16x16x32_bf16.  Shapes: fp32 gradients, one basis, d a multiple of 256, k of 4, and the limits of
-// gvq_ws_shape; whole 16-slice tiles only, the caller sends what is left of a range to the LDS-tiled kernels.
+// gvq_ws_shape.  The slices after the last whole 16-slice tile of a range (and the slice that ends past the gradient's
+// end) are one more tile, fetched with bounds-checked loads by one work-group: a second launch for them would cost a
+// fifth of the whole kernel's time (one work-group of the LDS-tiled kernel walking through all of U: 33 us).
 // The same scheme for Eq. (4) was tried and dropped: its 16 x d output tile leaves the compute unit in one burst
 // per tile, and no arrangement of those stores (direct, through LDS as whole rows, spread over the next tile's
 // products, fewer storing waves) came within 10 % of the LDS-tiled decompress kernels.
 #include "gvq_internal.h"
+
+#include <type_traits>
 
 #include "gvq_device.h"
 
@@ -29,7 +33,9 @@ struct WsArgs {
     const u4* Upack;         // the operand-order copy of U (layout at the pack kernel)
     const float* mu;         // [d]
     int64_t first;           // first slice
-    int64_t ntiles;          // 16-slice tiles
+    int64_t ntiles;          // whole 16-slice tiles inside the gradient
+    int64_t M;               // elements of the gradient
+    int tail_rows;           // slices after the last whole tile (0 .. 16; the last one may end past M)
     int d, k;
     float n_workers;
 };
@@ -91,20 +97,11 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
         }
     }
     drain_memory();   // U and the first tiles have arrived: the loop below inherits no wait
-    for (int buf = 0; t < a.ntiles; t += gridDim.x, buf = buf + 1 == nbuf ? 0 : buf + 1) {
-        // the tile to ask for (the current one again when there is none: the count in flight stays the same)
-        // and the buffer it goes to, which held the tile before this one
-        const int64_t ta = t + (int64_t)ahead * gridDim.x < a.ntiles ? t + (int64_t)ahead * gridDim.x : t;
-        const int bufa = buf == 0 ? nbuf - 1 : buf - 1;
-        // This wave's rows of the current tile: memory operations retire in order, and the requests younger
-        // than them are the copies of the tiles between (2 STEPS each) and one store per tile for the waves
-        // that add up a column tile.
-        if (ahead == 2) {
-            if (adds) wait_vmem_at_most<2 * STEPS + 2>(); else wait_vmem_at_most<2 * STEPS>();
-        } else {
-            if (adds) wait_vmem_at_most<1>(); else wait_vmem_at_most<0>();
-        }
-        __syncthreads();
+
+    // One tile out of buffer `buf`: products, partial results, their sum, and the store of its first `rows` slices.
+    // AHEAD: the pieces of tile `ta` are copied into buffer `bufa` between the products.
+    auto work_tile = [&](auto ahead_c, int buf, int64_t tile, int rows, int64_t ta, int bufa) {
+        constexpr bool AHEAD = decltype(ahead_c)::value;
         f4 acc[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
@@ -117,8 +114,10 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
             const f4 m0 = *(const f4*)(mrow + 32 * st), m1 = *(const f4*)(mrow + 32 * st + 16);
             // two pieces of the tile ahead per step, between the products: every wave is past the second
             // barrier of the tile that used that buffer
-            copy_piece(ta, bufa, 2 * st);
-            copy_piece(ta, bufa, 2 * st + 1);
+            if constexpr (AHEAD) {
+                copy_piece(ta, bufa, 2 * st);
+                copy_piece(ta, bufa, 2 * st + 1);
+            }
             u4 xh, xl;
             split8(x0 - m0, x1 - m1, xh, xl);
             const lbf8 bh = __builtin_bit_cast(lbf8, xh), bl = __builtin_bit_cast(lbf8, xl);
@@ -145,15 +144,56 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
 #pragma unroll
             for (int v = 1; v < WS_WAVES; ++v) s += *(const f4*)(prow + EW * v);
             const int c0 = 16 * w + 4 * kk;
-            const int64_t o = (a.first + 16 * t + n_) * a.k + c0;
+            const int64_t o = (a.first + 16 * tile + n_) * a.k + c0;
             float* Y = (float*)a.out;
-            if (c0 < a.k) {   // k is a multiple of 4; true for the lanes kk = 0 at least
+            if (c0 < a.k && n_ < rows) {   // k is a multiple of 4; true for the lanes kk = 0 at least
                 if (a.acc_in) s += *(const f4*)(a.acc_in + o);
                 *(f4*)(Y + o) = s;
             }
         }
+    };
+
+    for (int buf = 0; t < a.ntiles; t += gridDim.x, buf = buf + 1 == nbuf ? 0 : buf + 1) {
+        // the tile to ask for (the current one again when there is none: the count in flight stays the same)
+        // and the buffer it goes to, which held the tile before this one
+        const int64_t ta = t + (int64_t)ahead * gridDim.x < a.ntiles ? t + (int64_t)ahead * gridDim.x : t;
+        const int bufa = buf == 0 ? nbuf - 1 : buf - 1;
+        // This wave's rows of the current tile: memory operations retire in order, and the requests younger
+        // than them are the copies of the tiles between (2 STEPS each) and one store per tile for the waves
+        // that add up a column tile.
+        if (ahead == 2) {
+            if (adds) wait_vmem_at_most<2 * STEPS + 2>(); else wait_vmem_at_most<2 * STEPS>();
+        } else {
+            if (adds) wait_vmem_at_most<1>(); else wait_vmem_at_most<0>();
+        }
+        __syncthreads();
+        work_tile(std::true_type{}, buf, t, 16, ta, bufa);
     }
-    drain_memory();   // the last copies have no reader: let them land before the work-group's LDS is released
+    drain_memory();   // the last copies have no reader: let them land before the buffers are used again or released
+
+    // The slices after the last whole tile (fewer than 16, or 16 of which the last ends past M): one work-group
+    // fetches them with bounds-checked loads, zeros where there is nothing, and works on them like on any tile.
+    if (a.tail_rows > 0 && (int64_t)blockIdx.x == a.ntiles % gridDim.x) {
+        __syncthreads();   // every wave has read its last partial results
+        const int64_t s0 = a.first + 16 * a.ntiles;
+        for (int i = tid; i < 16 * (D / 4); i += 512) {
+            const int row = i / (D / 4), c4 = i - row * (D / 4);
+            const int64_t e = (s0 + row) * (int64_t)D + 4 * c4;
+            f4 v = {0.f, 0.f, 0.f, 0.f};
+            if (row < a.tail_rows) {
+                const float* g = (const float*)a.in + e;
+                if (e + 3 < a.M) v = *(const f4*)g;
+                else {
+                    if (e < a.M) v.x = g[0];
+                    if (e + 1 < a.M) v.y = g[1];
+                    if (e + 2 < a.M) v.z = g[2];
+                }
+            }
+            *(f4*)(xs + row * RS + 4 * c4) = v;
+        }
+        __syncthreads();
+        work_tile(std::false_type{}, 0, a.ntiles, a.tail_rows, 0, 0);
+    }
 }
 
 // --------------------------------------------------------------------------------------
@@ -231,7 +271,8 @@ static int launch_ws(const gvq_basis* h, const WsArgs& a, size_t lds, int nbuf, 
         GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         allowed = lds;
     }
-    const int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
+    int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
+    if (grid < 1) grid = 1;   // only the slices after the last whole tile
     hipLaunchKernelGGL(KERN, dim3((unsigned)grid), dim3(512), lds, st, a, nbuf);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
@@ -256,7 +297,7 @@ static int compress_ws_nt(const gvq_basis* h, const WsArgs& a, hipStream_t st)
     return launch_ws<compress_ws_kernel<STEPS, 2>>(h, a, lds, nbuf, st);
 }
 
-// Compresses the whole tiles at the start of the range; *done = the slices it took.
+// Compresses the range (as far as the gradient has slices); *done = the slices it took.
 int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
                            const float* comp_in, float* out, hipStream_t st, int64_t* done)
 {
@@ -264,8 +305,12 @@ int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, 
     a.in = grad; a.out = out; a.acc_in = comp_in; a.Upack = (const u4*)h->d_Uws; a.mu = h->d_mu;
     a.first = first_slice; a.ntiles = ws_tiles(h, first_slice, n_slices); a.d = h->d; a.k = h->k;
     a.n_workers = (float)n_workers;
-    *done = 16 * a.ntiles;
-    if (a.ntiles == 0) return GVQ_OK;
+    a.M = h->M;
+    const int64_t end = first_slice + n_slices < h->S ? first_slice + n_slices : h->S;
+    const int64_t tail = end - (first_slice + 16 * a.ntiles);   // 0 .. 15 whole slices and the one that ends past M
+    a.tail_rows = tail > 0 ? (int)tail : 0;
+    *done = 16 * a.ntiles + a.tail_rows;
+    if (*done == 0) return GVQ_OK;
     switch (h->d / 256) {
     case 1: return compress_ws_nt<1>(h, a, st);
     case 2: return compress_ws_nt<2>(h, a, st);
