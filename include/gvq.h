@@ -253,10 +253,9 @@ const char* gvq_strerror(int status);
  *             products where they keep up with memory (2dk/(4(d+k)) < 10 flop per byte),
  *             else products of two-term bf16 splits with fp32 accumulation (each product good to
  *             about 1e-5 of its magnitude, results within 1e-5 of the exact ones relative to the
- *             largest value, up to 2 times faster); 1 = always exact products; 2 = always the split,
- *             and compress takes the kernel that keeps U in registers wherever it can run (fp32
- *             gradients, one basis, d a multiple of 256; by default only where it is the faster one);
- *             3 = always the split, never that kernel;
+ *             largest value, up to 2 times faster); 1 = always exact products; 2 = always the split;
+ *             3 = always the split, and compress never takes the kernel that keeps U in registers
+ *             (its default for fp32 gradients with one basis and d a multiple of 256, for A/B timing);
  *   option 3: bit mask that sends every tile of a kernel family through its bounds-checked general loop
  *             instead of the branch-free loop over whole tiles (1: fp32-pipe compress, 2: bf16-pipe
  *             compress, 4: decompress); results are identical, for A/B timing;

@@ -768,8 +768,8 @@ size_t gvq_long_split_pack_halves(int d, int k)
 // Which matrix pipe: exact fp32 products while they keep up with memory (2dk / (4(d + k)) below 10
 // flop per byte; at 14, d = 256 and k = 32, the fp32 decompress already falls a quarter behind the
 // split one), the bf16 split above that.  Option 2 overrides: 1 = always fp32 products, 2 = always
-// the split, with the basis-stationary compress kernel (gvq_codec_ws.hip) wherever it can run, 3 = the
-// split, never that kernel.
+// the split, 3 = the split without the basis-stationary compress kernel (gvq_codec_ws.hip), which otherwise
+// takes the fp32 gradients of every shape it can run on.
 bool gvq_long_split(const gvq_basis* h)
 {
     const int mode = gvq_opt_long_mode();
@@ -921,10 +921,9 @@ int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers
                              int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
     const bool split = gvq_long_split(h), bf = h->dtype == GVQ_BF16;
-    // whole 16-slice tiles of fp32 gradients: U in registers, where that is the faster kernel (option 2: 2 = wherever it
-    // can run, 3 = nowhere)
+    // fp32 gradients in the shapes it takes: the kernel that keeps U in registers (option 2 = 3: never)
     const int mode = gvq_opt_long_mode();
-    if (split && !bf && gvq_ws_shape(h) && mode != 3 && (mode == 2 || gvq_ws_pays(h))) {
+    if (split && !bf && gvq_ws_shape(h) && mode != 3) {
         int64_t done = 0;
         const int rc = gvq_launch_compress_ws(h, grad, n_workers, first_slice, n_slices, comp_in, out, st, &done);
         if (rc != GVQ_OK) return rc;

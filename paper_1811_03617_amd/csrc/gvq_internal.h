@@ -84,8 +84,8 @@ int gvq_hip_fail(hipError_t e, const char* what);
 int gvq_opt_wg_per_cu();
 // Tiles per run in the MFMA kernels' schedule (0 = default).
 int gvq_opt_run_tiles();
-// LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split, with the
-// basis-stationary compress kernel wherever it can run, 3 = the bf16 split without that kernel.
+// LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split,
+// 3 = the bf16 split without the basis-stationary compress kernel.
 int gvq_opt_long_mode();
 // Bit mask: send every tile through the bounds-checked general phase (1: fp32-pipe compress, 2: bf16-pipe
 // compress, 4: decompress).
@@ -131,9 +131,8 @@ int gvq_launch_loss_long(const gvq_basis* h, const void* grad, int n_workers, fl
 int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices,
                                void* out, gvq_dtype_t odt, hipStream_t st);
 // Basis-stationary compress kernel (gvq_codec_ws.hip): U stays in registers, the gradient streams past in tiles
-// of 16 whole slices.  The launcher takes the whole tiles at the start of the range and reports the slices done.
+// of 16 whole slices.  The launcher reports the slices done (the whole range, as far as the gradient has slices).
 bool gvq_ws_shape(const gvq_basis* h);   // it can take this handle's shape
-bool gvq_ws_pays(const gvq_basis* h);    // ... and is the faster one there
 size_t gvq_ws_pack_halves(int d, int k);   // bf16 values of its operand-order copy of U
 int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st);
 int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,

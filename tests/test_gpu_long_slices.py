@@ -234,14 +234,17 @@ def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
     (256 * 500 + 3, 256, 32, 2),    # the smallest slice it takes
     (256 * 300, 256, 128, 2),       # too many column tiles for a wave's strip: the LDS-tiled kernels
     (512 * 100, 512, 52, 3),
-    (768 * 20 + 5, 768, 96, 2),     # one 16-slice tile, the rest to the LDS-tiled kernels
-    (768 * 10, 768, 96, 2),         # no whole tile
+    (768 * 20 + 5, 768, 96, 2),     # one whole tile, then 4 slices and one that ends after 5 elements
+    (768 * 10, 768, 96, 2),         # no whole tile: the tail tile alone
+    (768 * 31 + 767, 768, 96, 2),   # a tail of 16 slices, the last one element short
+    (768 * 32, 768, 96, 2),         # whole tiles only
+    (1024 * 47 + 2, 1024, 64, 2),   # two buffers in LDS instead of three
     (768 * 4113 + 700, 768, 96, 2), # more tiles than work-groups, several per work-group
 ])
 def test_basis_stationary_kernels(M, d, k, N):
     """fp32 gradients, one basis, d a multiple of 256, the bf16-split pipe by default: compress keeps U in
     registers and the gradient streams past in 16-slice tiles; compared with the oracle like every other route."""
-    for pipe in (0, 2):   # where it is the default, and wherever it can run
+    for pipe in (0, 2):   # the pipe picked from the shape, and the split forced
         assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
         try:
             _check_codec(_wl(M, d, k, N, 2), out_dtype="bf16")
