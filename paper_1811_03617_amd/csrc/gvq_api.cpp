@@ -154,7 +154,7 @@ int gvq_basis_create(gvq_basis_t** out, int64_t n_elems, int d, int k, int n_blo
             TRY(hipMalloc((void**)&h->d_Upc, sizeof(float) * B * pf));
             TRY(hipMalloc((void**)&h->d_Upd, sizeof(float) * B * pf));
             TRY(hipMalloc((void**)&h->d_Upb, sizeof(unsigned short) * B * 2 * gvq_long_split_pack_halves(d, k)));
-            if (gvq_ws_shape(h)) TRY(hipMalloc((void**)&h->d_Uws, sizeof(unsigned short) * gvq_ws_pack_halves(d, k)));
+            if (gvq_ws_alloc_halves(h)) TRY(hipMalloc((void**)&h->d_Uws, sizeof(unsigned short) * gvq_ws_alloc_halves(h)));
             if (n_blocks > 1) {
                 h->h_ltile = (int64_t*)malloc(sizeof(int64_t) * (B + 1));
                 if (!h->h_ltile) { rc = GVQ_ENOMEM; goto fail; }

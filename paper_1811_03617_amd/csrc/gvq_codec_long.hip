@@ -791,7 +791,7 @@ int gvq_launch_pack_long(const gvq_basis* h, hipStream_t st)
                            split_nt(h->k), nchunk, 128 * p, np, p);
         GVQ_HIP(hipGetLastError());
     }
-    if (gvq_ws_shape(h)) return gvq_launch_pack_ws(h, st);
+    if (gvq_ws_shape(h) || gvq_wsd_shape(h)) return gvq_launch_pack_ws(h, st);
     return GVQ_OK;
 }
 
@@ -966,6 +966,15 @@ int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t fi
                                void* out, gvq_dtype_t odt, hipStream_t st)
 {
     const bool split = gvq_long_split(h), bf = odt == GVQ_BF16;
+    // fp32 output in the shapes it takes: the kernel that keeps U in registers (option 2 = 3: never)
+    if (split && !bf && gvq_wsd_shape(h) && gvq_opt_long_mode() != 3) {
+        int64_t done = 0;
+        const int rc = gvq_launch_decompress_ws(h, comp, first_slice, n_slices, (float*)out, st, &done);
+        if (rc != GVQ_OK) return rc;
+        first_slice += done;
+        n_slices -= done;
+        if (n_slices <= 0) return GVQ_OK;
+    }
     const LongArgs a0 = long_args(h, comp, out, h->d_Upd, first_slice, n_slices);
     const unsigned short* Upd_split = h->d_Upb + (size_t)h->B * gvq_long_split_pack_halves(h->d, h->k);
     for (int p = 0; p < gvq_long_passes(h->k); ++p) {

@@ -1,5 +1,5 @@
-// Basis-stationary compress kernel for long slices (Section 3, "slice size": d = 768 in the paper's example) on
-// the bf16 matrix pipe: Eq. (2), y = U^T (x - mu/N).
+// Basis-stationary kernels for long slices (Section 3, "slice size": d = 768 in the paper's example) on
+// the bf16 matrix pipe: Eq. (2), y = U^T (x - mu/N), first; Eq. (4) further down.
 //
 // The LDS-tiled kernels of gvq_codec_long.hip stream U through LDS once per 128-slice tile and walk over the
 // gradient in 256-byte strips of 128 rows.  Here the roles are swapped.  A compute unit's register files hold
@@ -17,9 +17,8 @@
 // gvq_ws_shape.  The slices after the last whole 16-slice tile of a range (and the slice that ends past the gradient's
 // end) are one more tile, fetched with bounds-checked loads by one work-group: a second launch for them would cost a
 // fifth of the whole kernel's time (one work-group of the LDS-tiled kernel walking through all of U: 33 us).
-// The same scheme for Eq. (4) was tried and dropped: its 16 x d output tile leaves the compute unit in one burst
-// per tile, and no arrangement of those stores (direct, through LDS as whole rows, spread over the next tile's
-// products, fewer storing waves) came within 10 % of the LDS-tiled decompress kernels.
+// Eq. (4) has a kernel of the same kind further down (decompress_ws_kernel): there a wave owns an eighth of the
+// slice's elements for all comps, nothing has to be added up, and what matters is how the 16 x d results leave.
 #include "gvq_internal.h"
 
 #include <type_traits>
@@ -148,7 +147,11 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
             float* Y = (float*)a.out;
             if (c0 < a.k && n_ < rows) {   // k is a multiple of 4; true for the lanes kk = 0 at least
                 if (a.acc_in) s += *(const f4*)(a.acc_in + o);
+#ifdef WS_NT
+                __builtin_nontemporal_store(s, (f4*)(Y + o));
+#else
                 *(f4*)(Y + o) = s;
+#endif
             }
         }
     };
@@ -221,6 +224,201 @@ __global__ void pack_ws_kernel(const float* U, unsigned short* Uc, int d, int k,
     }
 }
 
+// --------------------------------------------------------------------------------------
+// decompress, Eq. (4): x = U y + mu, fp32 output.  Wave w keeps the rows 2 STEPS x 16 of U that belong to its
+// eighth of the slice (all comps) and produces that eighth of all 16 slices of a tile from the whole y tile: no
+// partial results to add.  The 16 x d results meet in LDS so that they leave as whole rows: wave w stores rows
+// 2w and 2w + 1 in runs of 1 KB.  Groups of WSD_IL consecutive tiles (which run side by side on neighbouring
+// compute units) interleave their slices: tile j of a group takes slices j, j + WSD_IL, ... of the group's
+// 16 WSD_IL, so that the chip writes one compact window row by row (a write-only probe of this pattern: 5.8 TB/s
+// against 4.9 - 5.1 for 48 KB runs per work-group and 3.4 - 4.4 for 64-byte pieces).  One barrier per tile: the
+// result tile is double-buffered, the y tiles sit in a ring of WSD_NY, and a tile's rows are stored between the
+// products of the tile after it, so that the store unit and the matrix pipe work at the same time (one burst of
+// stores per tile, with nothing computed meanwhile, was 13 % slower).
+// A tile's y (16 rows of k floats) is gathered global -> LDS by the load unit, one 128-bit word per lane: LDS word
+// YW row + c holds comps 4c .. 4c + 3 of the row's slice, YW = 8 NKS + 1 (odd: 16 lanes x 128 bits cover all banks),
+// and the words past k come from a zero word in global memory, so that a row reads as zeros up to 32 NKS comps.
+// LDS: os[2][16][d + 4] floats, ys[WSD_NY][YT] 128-bit words (YT: 16 YW rounded up to whole 64-lane copies), mus[d].
+// --------------------------------------------------------------------------------------
+struct WsdArgs {
+    const float* y;          // compressed gradient
+    float* out;              // gradient
+    const u4* Upack;         // the operand-order copy of U (layout at the pack kernel)
+    const float* zero;       // 4 floats of zeros
+    const float* mu;         // [d]
+    int64_t first;           // first slice
+    int64_t ntiles;          // whole 16-slice tiles inside the gradient
+    int64_t M;               // elements of the gradient
+    int tail_rows;           // slices after the last whole tile (0 .. 16; the last one may end past M)
+    int d, k;
+    int il;                  // tiles per interleave group
+};
+
+#define WSD_IL 16
+#define WSD_NY 4   // y tiles in LDS: one in use, three on their way
+
+template <int STEPS, int NKS>
+__global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
+{
+    extern __shared__ f4 smem[];
+    constexpr int D = 256 * STEPS, RS = D + WS_ROWPAD, EW = 32 * STEPS, NTI = 2 * STEPS;
+    constexpr int YW = 8 * NKS + 1, YC = (16 * YW + 63) / 64, YT = 64 * YC;   // words per row, 64-word copies, words
+    float* os = (float*)smem;            // [2][16][RS]
+    f4* ys = (f4*)(os + 2 * 16 * RS);    // [WSD_NY][YT]
+    float* mus = (float*)(ys + WSD_NY * YT);  // [D]
+    const int tid = threadIdx.x, lane = tid & 63, n_ = lane & 15, kk = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    u4 ua[NTI][NKS][2];
+#pragma unroll
+    for (int ti = 0; ti < NTI; ++ti)
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) ua[ti][ks][p] = a.Upack[((((size_t)w * NTI + ti) * NKS + ks) * 2 + p) * 64 + lane];
+    for (int e = tid; e < D; e += 512) mus[e] = a.mu[e];
+
+    // Slice `row` of tile `tile`, counted from a.first (see above); the tiles past the last whole group, and the
+    // tail tile, keep 16 consecutive slices.
+    const int64_t n_il = a.ntiles / a.il * a.il;
+    auto slice_of = [&](int64_t tile, int row) -> int64_t {
+        if (tile >= n_il) return 16 * tile + row;
+        const int64_t g = tile / a.il, j = tile - g * a.il;
+        return 16 * a.il * g + (int64_t)row * a.il + j;
+    };
+    // This wave's copies of a tile's y: the 64 words from 64 c on, c = w and w + 8 (the latter only exists for
+    // wave 0, and only when a tile has more than 512 words).
+    const int kq = a.k >> 2;
+    const unsigned int ys_off = (unsigned int)(size_t)(__attribute__((address_space(3))) void*)ys;
+    auto copy_y = [&](int64_t tile, int buf, int rows) {
+        for (int c = w; c < YC; c += 8) {
+            const int word = 64 * c + lane, row = word / YW, col = word - row * YW;
+            const float* src = a.zero;
+            if (row < rows && col < kq) src = a.y + (a.first + slice_of(tile, row)) * a.k + 4 * col;
+            copy_1k_to_lds(src, ys_off + 16u * (unsigned int)(buf * YT + 64 * c));
+        }
+    };
+
+    // Rows 2w and 2w + 1 of the result tile in os[buf] leave whole, piece i = 0 .. 2 STEPS - 1 at a time.
+    auto store_piece = [&](int buf, int64_t tile, int i) {
+        const int row = 2 * w + i / STEPS, q = i % STEPS;
+        const f4 v = *(const f4*)(os + (buf * 16 + row) * RS + q * 256 + lane * 4);
+        stream_store((f4*)(a.out + (a.first + slice_of(tile, row)) * (int64_t)D + q * 256 + lane * 4), v);
+    };
+    // The products of one tile out of ys[ybuf] into os[buf]; between them, when there is one, the stores of the tile
+    // before (`prev`, in the other result buffer): the store unit takes them while the matrix pipe works, instead of
+    // one burst per tile during which nothing is computed.
+    auto products = [&](int buf, int ybuf, bool have_prev, int64_t prev) {
+        f4 acc[NTI];
+        const float* mrow = mus + EW * w + 4 * kk;
+#pragma unroll
+        for (int ti = 0; ti < NTI; ++ti) acc[ti] = *(const f4*)(mrow + 16 * ti);
+        const f4* yr = ys + ybuf * YT + n_ * YW + kk;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            // lane (n, kk): comps 32 ks + 16 h + 4 kk .. + 3, h = 0, 1, of slice n
+            u4 yh, yl;
+            split8(yr[8 * ks], yr[8 * ks + 4], yh, yl);
+            const lbf8 bh = __builtin_bit_cast(lbf8, yh), bl = __builtin_bit_cast(lbf8, yl);
+#pragma unroll
+            for (int ti = 0; ti < NTI; ++ti)
+                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bl, acc[ti], 0, 0, 0);
+#pragma unroll
+            for (int ti = 0; ti < NTI; ++ti)
+                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][1]), bh, acc[ti], 0, 0, 0);
+#pragma unroll
+            for (int ti = 0; ti < NTI; ++ti)
+                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bh, acc[ti], 0, 0, 0);
+            if (have_prev) {
+#pragma unroll
+                for (int i = 0; i < 2 * STEPS; ++i)
+                    if (i * NKS / (2 * STEPS) == ks) store_piece(buf ^ 1, prev, i);
+            }
+        }
+        // register r of lane (n, kk) of row tile ti: element EW w + 16 ti + 4 kk + r of slice n
+        float* orow = os + (buf * 16 + n_) * RS + EW * w + 4 * kk;
+#pragma unroll
+        for (int ti = 0; ti < NTI; ++ti) *(f4*)(orow + 16 * ti) = acc[ti];
+    };
+
+    // this wave's copies per tile
+    const int ncopy = (w < YC ? 1 : 0) + (w + 8 < YC ? 1 : 0);
+    int64_t t = blockIdx.x;
+    if (t < a.ntiles) {
+        for (int p = 0; p < WSD_NY; ++p) {
+            const int64_t tp = t + (int64_t)p * gridDim.x;
+            copy_y(tp < a.ntiles ? tp : t, p, 16);
+        }
+    }
+    drain_memory();   // U, and the first y tiles: the loop below inherits no wait
+    __syncthreads();
+    int buf = 0;
+    for (int ybuf = 0; t < a.ntiles; t += gridDim.x, buf ^= 1, ybuf = ybuf + 1 == WSD_NY ? 0 : ybuf + 1) {
+        products(buf, ybuf, t != (int64_t)blockIdx.x, t - gridDim.x);
+        // The y tile after this one was asked for WSD_NY - 1 tiles ago.  Requests retire in order, and the younger
+        // ones are the stores of WSD_NY - 1 tiles and the copies of the WSD_NY - 2 y tiles between.
+        constexpr int younger = (WSD_NY - 1) * 2 * STEPS;
+        if (ncopy == 0) wait_vmem_at_most<younger>();
+        else if (ncopy == 1) wait_vmem_at_most<younger + (WSD_NY - 2)>();
+        else wait_vmem_at_most<younger + 2 * (WSD_NY - 2)>();
+        __syncthreads();
+        // WSD_NY tiles on, into the buffer that this tile's products have just read
+        const int64_t ta = t + (int64_t)WSD_NY * gridDim.x;
+        copy_y(ta < a.ntiles ? ta : t, ybuf, 16);
+    }
+    // the last tile's rows (its barrier has passed)
+    if ((int64_t)blockIdx.x < a.ntiles) {
+#pragma unroll
+        for (int i = 0; i < 2 * STEPS; ++i) store_piece(buf ^ 1, t - gridDim.x, i);
+    }
+    drain_memory();   // the last copies have no reader: let them land before the buffers are used again or released
+
+    // The slices after the last whole tile: the same work by one work-group, with bounds-checked stores.
+    if (a.tail_rows > 0 && (int64_t)blockIdx.x == a.ntiles % gridDim.x) {
+        __syncthreads();   // every wave is past its last reads of both buffers
+        copy_y(a.ntiles, 0, a.tail_rows);
+        drain_memory();
+        __syncthreads();
+        products(0, 0, false, 0);
+        __syncthreads();
+        for (int i = 0; i < 2 * STEPS; ++i) {
+            const int row = 2 * w + i / STEPS, q = i % STEPS;
+            if (row >= a.tail_rows) continue;
+            const f4 v = *(const f4*)(os + row * RS + q * 256 + lane * 4);
+            const int64_t e = (a.first + 16 * a.ntiles + row) * (int64_t)D + q * 256 + lane * 4;
+            if (e + 3 < a.M) *(f4*)(a.out + e) = v;
+            else {
+                if (e < a.M) a.out[e] = v.x;
+                if (e + 1 < a.M) a.out[e + 1] = v.y;
+                if (e + 2 < a.M) a.out[e + 2] = v.z;
+            }
+        }
+    }
+}
+
+// The operand-order copy of U for the kernel above, 8 bf16 per 128-bit word, terms as in pack_ws_kernel.
+// Ud[w][ti][ks][p][lane (m, kk)][j] = U[EW w + 16 ti + m][32 ks + r(kk, j)], r(kk, j) = 16 (j / 4) + 4 kk + j % 4.
+__global__ void pack_wsd_kernel(const float* U, unsigned short* Ud, int d, int k, int NKS)
+{
+    const int EW = d / 8, NTI = d / 128;
+    const size_t n = (size_t)WS_WAVES * NTI * NKS * 2 * 512;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += (size_t)gridDim.x * blockDim.x) {
+        const int j = (int)(q & 7), lane = (int)((q >> 3) & 63), m = lane & 15, kk = lane >> 4, p = (int)((q >> 9) & 1);
+        size_t g = q >> 10;
+        const int ks = (int)(g % NKS); g /= NKS;
+        const int ti = (int)(g % NTI), w = (int)(g / NTI);
+        const int e = EW * w + 16 * ti + m, comp = 32 * ks + 16 * (j >> 2) + 4 * kk + (j & 3);
+        unsigned short v = 0;
+        if (comp < k) {
+            const float u = U[(size_t)e * k + comp];
+            const unsigned int t0 = f32_to_bf16_rne(u);
+            v = (unsigned short)(p == 0 ? t0 : f32_to_bf16_rne(u - __uint_as_float(t0 << 16)));
+        }
+        Ud[q] = v;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 8) Ud[n + threadIdx.x] = 0;   // the zero word of WsdArgs
+}
+
 // ======================================================================================
 // host side
 // ======================================================================================
@@ -228,8 +426,12 @@ static int ws_nt(int k) { const int nt = (k + 15) / 16; return nt + (nt & 1); } 
 
 // LDS: nbuf tiles of 16 padded rows, and mu
 static size_t ws_lds(int d, int nbuf) { return sizeof(float) * ((size_t)nbuf * 16 * (d + WS_ROWPAD) + d); }
-// Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two
-static int ws_nbuf(int d) { return ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
+// Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two; two also at d = 512, where
+// they measure 3 % faster (at d = 256 two are 20 % slower, at d = 768 2 % slower)
+#ifndef WS_NBUF
+#define WS_NBUF 3
+#endif
+static int ws_nbuf(int d) { return WS_NBUF == 3 && ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
 
 // One basis, d in {256, 512, 768, 1024}, k a multiple of 4, U fits the registers of 8 waves (d/256 x NT words of
 // 8 registers, at most 18), and a wave's partial result fits its strip of the tile (16 floats per column tile,
@@ -244,10 +446,35 @@ bool gvq_ws_shape(const gvq_basis* h)
 // bf16 values of the operand-order copy
 size_t gvq_ws_pack_halves(int d, int k) { return (size_t)WS_WAVES * (d / 256) * ws_nt(k) * 2 * 512; }
 
+// decompress: one basis, d in {256, 512, 768, 1024}, k a multiple of 4 up to 128 (a tile's y is one 128-bit word
+// per thread), U fits the registers of 8 waves (d/128 x ceil(k/32) words of 8 registers, at most 18).
+static int wsd_nks(int k) { return (k + 31) / 32; }
+bool gvq_wsd_shape(const gvq_basis* h)
+{
+    if (h->B != 1 || h->d % 256 != 0 || h->d > 1024 || h->k % 4 != 0 || h->k > 128) return false;
+    return (h->d / 128) * wsd_nks(h->k) <= 18;
+}
+// ... and 8 more for a 128-bit word of zeros
+static size_t wsd_copy_halves(int d, int k) { return (size_t)WS_WAVES * (d / 128) * wsd_nks(k) * 2 * 512; }
+size_t gvq_wsd_pack_halves(int d, int k) { return wsd_copy_halves(d, k) + 8; }
+// d_Uws holds the compress copy (if that kernel takes the shape), then the decompress copy
+static size_t wsd_offset_halves(const gvq_basis* h) { return gvq_ws_shape(h) ? gvq_ws_pack_halves(h->d, h->k) : 0; }
+size_t gvq_ws_alloc_halves(const gvq_basis* h)
+{
+    return wsd_offset_halves(h) + (gvq_wsd_shape(h) ? gvq_wsd_pack_halves(h->d, h->k) : 0);
+}
+
 int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st)
 {
-    hipLaunchKernelGGL(pack_ws_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws, h->d, h->k, ws_nt(h->k));
-    GVQ_HIP(hipGetLastError());
+    if (gvq_ws_shape(h)) {
+        hipLaunchKernelGGL(pack_ws_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws, h->d, h->k, ws_nt(h->k));
+        GVQ_HIP(hipGetLastError());
+    }
+    if (gvq_wsd_shape(h)) {
+        hipLaunchKernelGGL(pack_wsd_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws + wsd_offset_halves(h), h->d,
+                           h->k, wsd_nks(h->k));
+        GVQ_HIP(hipGetLastError());
+    }
     return GVQ_OK;
 }
 
@@ -312,5 +539,59 @@ int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, 
     case 2: return compress_ws_nt<2>(h, a, st);
     case 3: return compress_ws_nt<3>(h, a, st);
     default: return compress_ws_nt<4>(h, a, st);
+    }
+}
+
+template <int STEPS, int NKS>
+static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
+{
+    constexpr int D = 256 * STEPS;
+    constexpr size_t lds = sizeof(float) * (2 * 16 * (D + WS_ROWPAD) + WSD_NY * 4 * 64 * ((16 * (8 * NKS + 1) + 63) / 64) + D);
+    static_assert(lds <= 160 * 1024, "LDS");
+    static bool allowed = false;
+    if (!allowed) {
+        GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        allowed = true;
+    }
+    int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS>), dim3((unsigned)grid), dim3(512), lds, st, a);
+    GVQ_HIP(hipGetLastError());
+    return GVQ_OK;
+}
+
+template <int STEPS>
+static int decompress_ws_nks(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
+{
+    // the shapes gvq_wsd_shape lets through: 2 STEPS x NKS <= 18, NKS <= 4
+    switch (wsd_nks(h->k)) {
+    case 1: return launch_wsd<STEPS, 1>(h, a, st);
+    case 2: return launch_wsd<STEPS, 2>(h, a, st);
+    case 3: if constexpr (STEPS <= 3) return launch_wsd<STEPS, 3>(h, a, st); else break;
+    case 4: if constexpr (STEPS <= 2) return launch_wsd<STEPS, 4>(h, a, st); else break;
+    }
+    return GVQ_EINVAL;
+}
+
+// Decompresses the range into fp32 (as far as the gradient has slices); *done = the slices it took.
+int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, float* out,
+                             hipStream_t st, int64_t* done)
+{
+    WsdArgs a;
+    a.y = comp; a.out = out; a.Upack = (const u4*)(h->d_Uws + wsd_offset_halves(h)); a.mu = h->d_mu;
+    a.zero = (const float*)(h->d_Uws + wsd_offset_halves(h) + wsd_copy_halves(h->d, h->k));
+    a.first = first_slice; a.ntiles = ws_tiles(h, first_slice, n_slices); a.M = h->M; a.d = h->d; a.k = h->k;
+    const int64_t end = first_slice + n_slices < h->S ? first_slice + n_slices : h->S;
+    const int64_t tail = end - (first_slice + 16 * a.ntiles);
+    a.tail_rows = tail > 0 ? (int)tail : 0;
+    a.il = gvq_opt_interleave() > 0 ? gvq_opt_interleave() : WSD_IL;
+    *done = 16 * a.ntiles + a.tail_rows;
+    if (*done == 0) return GVQ_OK;
+    switch (h->d / 256) {
+    case 1: return decompress_ws_nks<1>(h, a, st);
+    case 2: return decompress_ws_nks<2>(h, a, st);
+    case 3: return decompress_ws_nks<3>(h, a, st);
+    default: return decompress_ws_nks<4>(h, a, st);
     }
 }
