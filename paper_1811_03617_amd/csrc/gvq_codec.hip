@@ -1481,6 +1481,17 @@ static int streaming_grid(const gvq_basis* h, int64_t tiles, int most = 0)
     int64_t want = (tiles + WAVES_PER_WG - 1) / WAVES_PER_WG;  // at least one tile per wave
     int64_t cap = (int64_t)h->num_cu * per_cu;
     int64_t g = want < cap ? want : cap;
+    // A short launch (few rounds of tiles per wave) ends with a round in which most waves have nothing left: a
+    // grid up to an eighth smaller whose last round is full moves the same bytes without that tail.
+    if (gvq_opt_wg_per_cu() <= 0 && g == cap && tiles / (cap * WAVES_PER_WG) < 32) {
+        int64_t best = g, best_idle = -1;
+        for (int64_t c = cap; c >= cap - cap / 8; --c) {
+            const int64_t waves = c * WAVES_PER_WG, rounds = (tiles + waves - 1) / waves;
+            const int64_t idle = (rounds * waves - tiles) * cap / c;   // wave-rounds wasted, scaled to the full grid
+            if (best_idle < 0 || idle < best_idle) { best = c; best_idle = idle; }
+        }
+        g = best;
+    }
     return (int)(g < 1 ? 1 : g);
 }
 
