@@ -55,7 +55,10 @@ __device__ __forceinline__ void copy_1k_to_lds(const void* src_lane, unsigned in
 // --------------------------------------------------------------------------------------
 // compress.  LDS: xs[2][16][d + 4] floats, part[8][NT][64] 128-bit words, mus[d] floats.
 // --------------------------------------------------------------------------------------
-template <int STEPS, int NT>
+// EXACT: fp32 products on v_mfma_f32_16x16x4_f32 instead of the bf16 split; U then sits in the same registers as
+// floats (word [st][nt][h], register r: U[EW w + 32 st + 16 h + 4 kk + r][16 nt + m] for lane (m, kk)), and each of a
+// lane's 8 floats of x per step is the B operand of one product.
+template <int STEPS, int NT, bool EXACT>
 __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
 {
     extern __shared__ f4 smem[];
@@ -117,18 +120,30 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
                 copy_piece(ta, bufa, 2 * st);
                 copy_piece(ta, bufa, 2 * st + 1);
             }
-            u4 xh, xl;
-            split8(x0 - m0, x1 - m1, xh, xl);
-            const lbf8 bh = __builtin_bit_cast(lbf8, xh), bl = __builtin_bit_cast(lbf8, xl);
+            if constexpr (EXACT) {
+                const f4 xc[2] = {x0 - m0, x1 - m1};
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bl, acc[nt], 0, 0, 0);
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][1]), bh, acc[nt], 0, 0, 0);
+                    for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bh, acc[nt], 0, 0, 0);
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(us[st][nt][h][r]), xc[h][r],
+                                                                           acc[nt], 0, 0, 0);
+            } else {
+                u4 xh, xl;
+                split8(x0 - m0, x1 - m1, xh, xl);
+                const lbf8 bh = __builtin_bit_cast(lbf8, xh), bl = __builtin_bit_cast(lbf8, xl);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bl, acc[nt], 0, 0, 0);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][1]), bh, acc[nt], 0, 0, 0);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, us[st][nt][0]), bh, acc[nt], 0, 0, 0);
+            }
         }
         // The partial result goes where this wave's strip of x was: nobody else reads that strip, and this wave
         // is done with it.  Register r of lane (n, kk) of column tile nt: row n, float EW w + 16 nt + 4 kk + r.
@@ -257,7 +272,9 @@ struct WsdArgs {
 #define WSD_IL 16
 #define WSD_NY 4   // y tiles in LDS: one in use, three on their way
 
-template <int STEPS, int NKS>
+// EXACT: fp32 products on v_mfma_f32_16x16x4_f32; U's words then hold floats, word [ti][ks][h], register r:
+// U[EW w + 16 ti + m][32 ks + 16 h + 4 kk + r] for lane (m, kk).
+template <int STEPS, int NKS, bool EXACT>
 __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
 {
     extern __shared__ f4 smem[];
@@ -317,18 +334,32 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             // lane (n, kk): comps 32 ks + 16 h + 4 kk .. + 3, h = 0, 1, of slice n
-            u4 yh, yl;
-            split8(yr[8 * ks], yr[8 * ks + 4], yh, yl);
-            const lbf8 bh = __builtin_bit_cast(lbf8, yh), bl = __builtin_bit_cast(lbf8, yl);
+            if constexpr (EXACT) {
+                const f4 yc[2] = {yr[8 * ks], yr[8 * ks + 4]};
 #pragma unroll
-            for (int ti = 0; ti < NTI; ++ti)
-                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bl, acc[ti], 0, 0, 0);
+                for (int h = 0; h < 2; ++h) {
+                    if (32 * ks + 16 * h >= a.k) continue;   // 16 comps that do not exist (k = 16: half the products)
 #pragma unroll
-            for (int ti = 0; ti < NTI; ++ti)
-                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][1]), bh, acc[ti], 0, 0, 0);
+                    for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int ti = 0; ti < NTI; ++ti)
-                acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bh, acc[ti], 0, 0, 0);
+                        for (int ti = 0; ti < NTI; ++ti)
+                            acc[ti] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(ua[ti][ks][h][r]), yc[h][r],
+                                                                           acc[ti], 0, 0, 0);
+                }
+            } else {
+                u4 yh, yl;
+                split8(yr[8 * ks], yr[8 * ks + 4], yh, yl);
+                const lbf8 bh = __builtin_bit_cast(lbf8, yh), bl = __builtin_bit_cast(lbf8, yl);
+#pragma unroll
+                for (int ti = 0; ti < NTI; ++ti)
+                    acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bl, acc[ti], 0, 0, 0);
+#pragma unroll
+                for (int ti = 0; ti < NTI; ++ti)
+                    acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][1]), bh, acc[ti], 0, 0, 0);
+#pragma unroll
+                for (int ti = 0; ti < NTI; ++ti)
+                    acc[ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lbf8, ua[ti][ks][0]), bh, acc[ti], 0, 0, 0);
+            }
             if (have_prev) {
 #pragma unroll
                 for (int i = 0; i < 2 * STEPS; ++i)
@@ -398,7 +429,7 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
 
 // The operand-order copy of U for the kernel above, 8 bf16 per 128-bit word, terms as in pack_ws_kernel.
 // Ud[w][ti][ks][p][lane (m, kk)][j] = U[EW w + 16 ti + m][32 ks + r(kk, j)], r(kk, j) = 16 (j / 4) + 4 kk + j % 4.
-__global__ void pack_wsd_kernel(const float* U, unsigned short* Ud, int d, int k, int NKS)
+__global__ void pack_wsd_kernel(const float* U, unsigned short* Ud, int d, int k, int NKS, size_t zero_at)
 {
     const int EW = d / 8, NTI = d / 128;
     const size_t n = (size_t)WS_WAVES * NTI * NKS * 2 * 512;
@@ -416,7 +447,39 @@ __global__ void pack_wsd_kernel(const float* U, unsigned short* Ud, int d, int k
         }
         Ud[q] = v;
     }
-    if (blockIdx.x == 0 && threadIdx.x < 8) Ud[n + threadIdx.x] = 0;   // the zero word of WsdArgs
+    if (blockIdx.x == 0 && threadIdx.x < 8) Ud[zero_at + threadIdx.x] = 0;   // the zero word of WsdArgs, after both copies
+}
+
+// The fp32 copy of U for decompress_ws_kernel<.., EXACT = true>.
+// Ude[w][ti][ks][h][lane (m, kk)][r] = U[EW w + 16 ti + m][32 ks + 16 h + 4 kk + r]; zero where comp >= k.
+__global__ void pack_wsd_exact_kernel(const float* U, float* Ue, int d, int k, int NKS)
+{
+    const int EW = d / 8, NTI = d / 128;
+    const size_t n = (size_t)WS_WAVES * NTI * NKS * 2 * 256;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(q & 3), lane = (int)((q >> 2) & 63), m = lane & 15, kk = lane >> 4, h = (int)((q >> 8) & 1);
+        size_t g = q >> 9;
+        const int ks = (int)(g % NKS); g /= NKS;
+        const int ti = (int)(g % NTI), w = (int)(g / NTI);
+        const int e = EW * w + 16 * ti + m, comp = 32 * ks + 16 * h + 4 * kk + r;
+        Ue[q] = comp < k ? U[(size_t)e * k + comp] : 0.f;
+    }
+}
+
+// The fp32 copy of U for compress_ws_kernel<.., EXACT = true>: same words as the bf16 copy, each holding 4 floats.
+// Ue[w][st][nt][h][lane (m, kk)][r] = U[EW w + 32 st + 16 h + 4 kk + r][16 nt + m]; zero where comp >= k.
+__global__ void pack_ws_exact_kernel(const float* U, float* Ue, int d, int k, int NT)
+{
+    const int EW = d / 8, STEPS = d / 256;
+    const size_t n = (size_t)WS_WAVES * STEPS * NT * 2 * 256;
+    for (size_t q = (size_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(q & 3), lane = (int)((q >> 2) & 63), m = lane & 15, kk = lane >> 4, h = (int)((q >> 8) & 1);
+        size_t g = q >> 9;
+        const int nt = (int)(g % NT); g /= NT;
+        const int st = (int)(g % STEPS), w = (int)(g / STEPS);
+        const int e = EW * w + 32 * st + 16 * h + 4 * kk + r, comp = 16 * nt + m;
+        Ue[q] = comp < k ? U[(size_t)e * k + comp] : 0.f;
+    }
 }
 
 // ======================================================================================
@@ -456,9 +519,9 @@ bool gvq_wsd_shape(const gvq_basis* h)
 }
 // ... and 8 more for a 128-bit word of zeros
 static size_t wsd_copy_halves(int d, int k) { return (size_t)WS_WAVES * (d / 128) * wsd_nks(k) * 2 * 512; }
-size_t gvq_wsd_pack_halves(int d, int k) { return wsd_copy_halves(d, k) + 8; }
-// d_Uws holds the compress copy (if that kernel takes the shape), then the decompress copy
-static size_t wsd_offset_halves(const gvq_basis* h) { return gvq_ws_shape(h) ? gvq_ws_pack_halves(h->d, h->k) : 0; }
+size_t gvq_wsd_pack_halves(int d, int k) { return 2 * wsd_copy_halves(d, k) + 8; }   // bf16 split, fp32, zeros
+// d_Uws holds the two compress copies (bf16 split, then fp32; if that kernel takes the shape), then the decompress copy
+static size_t wsd_offset_halves(const gvq_basis* h) { return gvq_ws_shape(h) ? 2 * gvq_ws_pack_halves(h->d, h->k) : 0; }
 size_t gvq_ws_alloc_halves(const gvq_basis* h)
 {
     return wsd_offset_halves(h) + (gvq_wsd_shape(h) ? gvq_wsd_pack_halves(h->d, h->k) : 0);
@@ -469,10 +532,17 @@ int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st)
     if (gvq_ws_shape(h)) {
         hipLaunchKernelGGL(pack_ws_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws, h->d, h->k, ws_nt(h->k));
         GVQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(pack_ws_exact_kernel, dim3(256), dim3(256), 0, st, h->d_U,
+                           (float*)(h->d_Uws + gvq_ws_pack_halves(h->d, h->k)), h->d, h->k, ws_nt(h->k));
+        GVQ_HIP(hipGetLastError());
     }
     if (gvq_wsd_shape(h)) {
         hipLaunchKernelGGL(pack_wsd_kernel, dim3(256), dim3(256), 0, st, h->d_U, h->d_Uws + wsd_offset_halves(h), h->d,
-                           h->k, wsd_nks(h->k));
+                           h->k, wsd_nks(h->k), 2 * wsd_copy_halves(h->d, h->k));
+        GVQ_HIP(hipGetLastError());
+        hipLaunchKernelGGL(pack_wsd_exact_kernel, dim3(256), dim3(256), 0, st, h->d_U,
+                           (float*)(h->d_Uws + wsd_offset_halves(h) + wsd_copy_halves(h->d, h->k)), h->d, h->k,
+                           wsd_nks(h->k));
         GVQ_HIP(hipGetLastError());
     }
     return GVQ_OK;
@@ -501,31 +571,43 @@ static int launch_ws(const gvq_basis* h, const WsArgs& a, size_t lds, int nbuf, 
     return GVQ_OK;
 }
 
-template <int STEPS>
+template <int STEPS, bool EXACT>
 static int compress_ws_nt(const gvq_basis* h, const WsArgs& a, hipStream_t st)
 {
     const int NT = ws_nt(h->k), nbuf = ws_nbuf(256 * STEPS);
     const size_t lds = ws_lds(256 * STEPS, nbuf);
     // the shapes gvq_ws_shape lets through: 16 NT <= 32 STEPS, and STEPS x NT <= 18
     if constexpr (STEPS == 4) {
-        if (NT == 4) return launch_ws<compress_ws_kernel<4, 4>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<4, 4, EXACT>>(h, a, lds, nbuf, st);
     }
     if constexpr (STEPS == 3) {
-        if (NT == 6) return launch_ws<compress_ws_kernel<3, 6>>(h, a, lds, nbuf, st);
-        if (NT == 4) return launch_ws<compress_ws_kernel<3, 4>>(h, a, lds, nbuf, st);
+        if (NT == 6) return launch_ws<compress_ws_kernel<3, 6, EXACT>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<3, 4, EXACT>>(h, a, lds, nbuf, st);
     }
     if constexpr (STEPS == 2) {
-        if (NT == 4) return launch_ws<compress_ws_kernel<2, 4>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<2, 4, EXACT>>(h, a, lds, nbuf, st);
     }
-    return launch_ws<compress_ws_kernel<STEPS, 2>>(h, a, lds, nbuf, st);
+    return launch_ws<compress_ws_kernel<STEPS, 2, EXACT>>(h, a, lds, nbuf, st);
+}
+
+template <bool EXACT>
+static int compress_ws_steps(const gvq_basis* h, const WsArgs& a, hipStream_t st)
+{
+    switch (h->d / 256) {
+    case 1: return compress_ws_nt<1, EXACT>(h, a, st);
+    case 2: return compress_ws_nt<2, EXACT>(h, a, st);
+    case 3: return compress_ws_nt<3, EXACT>(h, a, st);
+    default: return compress_ws_nt<4, EXACT>(h, a, st);
+    }
 }
 
 // Compresses the range (as far as the gradient has slices); *done = the slices it took.
 int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
-                           const float* comp_in, float* out, hipStream_t st, int64_t* done)
+                           const float* comp_in, float* out, bool exact, hipStream_t st, int64_t* done)
 {
     WsArgs a;
-    a.in = grad; a.out = out; a.acc_in = comp_in; a.Upack = (const u4*)h->d_Uws; a.mu = h->d_mu;
+    a.in = grad; a.out = out; a.acc_in = comp_in; a.mu = h->d_mu;
+    a.Upack = (const u4*)(h->d_Uws + (exact ? gvq_ws_pack_halves(h->d, h->k) : 0));
     a.first = first_slice; a.ntiles = ws_tiles(h, first_slice, n_slices); a.d = h->d; a.k = h->k;
     a.n_workers = (float)n_workers;
     a.M = h->M;
@@ -534,15 +616,10 @@ int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, 
     a.tail_rows = tail > 0 ? (int)tail : 0;
     *done = 16 * a.ntiles + a.tail_rows;
     if (*done == 0) return GVQ_OK;
-    switch (h->d / 256) {
-    case 1: return compress_ws_nt<1>(h, a, st);
-    case 2: return compress_ws_nt<2>(h, a, st);
-    case 3: return compress_ws_nt<3>(h, a, st);
-    default: return compress_ws_nt<4>(h, a, st);
-    }
+    return exact ? compress_ws_steps<true>(h, a, st) : compress_ws_steps<false>(h, a, st);
 }
 
-template <int STEPS, int NKS>
+template <int STEPS, int NKS, bool EXACT>
 static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
 {
     constexpr int D = 256 * STEPS;
@@ -550,37 +627,49 @@ static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
     static_assert(lds <= 160 * 1024, "LDS");
     static bool allowed = false;
     if (!allowed) {
-        GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS>,
+        GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS, EXACT>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         allowed = true;
     }
     int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS>), dim3((unsigned)grid), dim3(512), lds, st, a);
+    hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS, EXACT>), dim3((unsigned)grid), dim3(512), lds, st, a);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
 
-template <int STEPS>
+template <int STEPS, bool EXACT>
 static int decompress_ws_nks(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
 {
     // the shapes gvq_wsd_shape lets through: 2 STEPS x NKS <= 18, NKS <= 4
     switch (wsd_nks(h->k)) {
-    case 1: return launch_wsd<STEPS, 1>(h, a, st);
-    case 2: return launch_wsd<STEPS, 2>(h, a, st);
-    case 3: if constexpr (STEPS <= 3) return launch_wsd<STEPS, 3>(h, a, st); else break;
-    case 4: if constexpr (STEPS <= 2) return launch_wsd<STEPS, 4>(h, a, st); else break;
+    case 1: return launch_wsd<STEPS, 1, EXACT>(h, a, st);
+    case 2: return launch_wsd<STEPS, 2, EXACT>(h, a, st);
+    case 3: if constexpr (STEPS <= 3) return launch_wsd<STEPS, 3, EXACT>(h, a, st); else break;
+    case 4: if constexpr (STEPS <= 2) return launch_wsd<STEPS, 4, EXACT>(h, a, st); else break;
     }
     return GVQ_EINVAL;
 }
 
+template <bool EXACT>
+static int decompress_ws_steps(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
+{
+    switch (h->d / 256) {
+    case 1: return decompress_ws_nks<1, EXACT>(h, a, st);
+    case 2: return decompress_ws_nks<2, EXACT>(h, a, st);
+    case 3: return decompress_ws_nks<3, EXACT>(h, a, st);
+    default: return decompress_ws_nks<4, EXACT>(h, a, st);
+    }
+}
+
 // Decompresses the range into fp32 (as far as the gradient has slices); *done = the slices it took.
 int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, float* out,
-                             hipStream_t st, int64_t* done)
+                             bool exact, hipStream_t st, int64_t* done)
 {
     WsdArgs a;
-    a.y = comp; a.out = out; a.Upack = (const u4*)(h->d_Uws + wsd_offset_halves(h)); a.mu = h->d_mu;
-    a.zero = (const float*)(h->d_Uws + wsd_offset_halves(h) + wsd_copy_halves(h->d, h->k));
+    const size_t copy = wsd_copy_halves(h->d, h->k);
+    a.y = comp; a.out = out; a.Upack = (const u4*)(h->d_Uws + wsd_offset_halves(h) + (exact ? copy : 0)); a.mu = h->d_mu;
+    a.zero = (const float*)(h->d_Uws + wsd_offset_halves(h) + 2 * copy);
     a.first = first_slice; a.ntiles = ws_tiles(h, first_slice, n_slices); a.M = h->M; a.d = h->d; a.k = h->k;
     const int64_t end = first_slice + n_slices < h->S ? first_slice + n_slices : h->S;
     const int64_t tail = end - (first_slice + 16 * a.ntiles);
@@ -588,10 +677,5 @@ int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t firs
     a.il = gvq_opt_interleave() > 0 ? gvq_opt_interleave() : WSD_IL;
     *done = 16 * a.ntiles + a.tail_rows;
     if (*done == 0) return GVQ_OK;
-    switch (h->d / 256) {
-    case 1: return decompress_ws_nks<1>(h, a, st);
-    case 2: return decompress_ws_nks<2>(h, a, st);
-    case 3: return decompress_ws_nks<3>(h, a, st);
-    default: return decompress_ws_nks<4>(h, a, st);
-    }
+    return exact ? decompress_ws_steps<true>(h, a, st) : decompress_ws_steps<false>(h, a, st);
 }

@@ -137,10 +137,10 @@ size_t gvq_ws_pack_halves(int d, int k);   // bf16 values of its operand-order c
 bool gvq_wsd_shape(const gvq_basis* h);  // the decompress kernel of the same kind (fp32 output) can take the shape
 size_t gvq_ws_alloc_halves(const gvq_basis* h);   // bf16 values of d_Uws: both kernels' copies
 int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, float* out,
-                             hipStream_t st, int64_t* done);
+                             bool exact, hipStream_t st, int64_t* done);
 int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st);
 int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
-                           const float* comp_in, float* out, hipStream_t st, int64_t* done);
+                           const float* comp_in, float* out, bool exact, hipStream_t st, int64_t* done);
 int gvq_large_groups(int d);
 size_t gvq_large_partial_doubles(int d, int chunks);   // per basis
 int gvq_launch_moments_large(gvq_basis* h, const void* const* grads, int L, hipStream_t st);

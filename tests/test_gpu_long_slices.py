@@ -244,7 +244,8 @@ def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
 def test_basis_stationary_kernels(M, d, k, N):
     """fp32 gradients, one basis, d a multiple of 256, the bf16-split pipe: compress, and decompress into fp32, keep U
     in registers while the gradient streams past in 16-slice tiles; compared with the oracle like every other route."""
-    for pipe, out_dtype in ((0, "f32"), (2, "bf16"), (2, "f32")):   # the pipe picked from the shape, and the split forced
+    # the pipe picked from the shape, exact fp32 products, the bf16 split
+    for pipe, out_dtype in ((0, "f32"), (1, "f32"), (2, "bf16"), (2, "f32")):
         assert gvq.lib().gvq_set_option(2, pipe) == gvq.OK
         try:
             _check_codec(_wl(M, d, k, N, 2), out_dtype=out_dtype)
