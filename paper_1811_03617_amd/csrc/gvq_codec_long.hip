@@ -837,12 +837,11 @@ template <auto KERN>
 static int launch_long(const gvq_basis* h, const LongArgs& a, int NT, hipStream_t st, int most = 0)
 {
     const size_t lds = sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * (size_t)a.nchunk * LC;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static gvq_once_per_device once;
+    if (once.first(h->device)) {
         // the largest slice needs 8 KB NT + 4 KB: allow it once, for every later launch
         GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)(sizeof(f4) * 2 * 4 * NT * 64 + sizeof(float) * GVQ_MAX_D)));
-        attr_set = true;
     }
     int per_cu = gvq_opt_wg_per_cu();
     if (per_cu <= 0) {

@@ -162,11 +162,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
             float* Y = (float*)a.out;
             if (c0 < a.k && n_ < rows) {   // k is a multiple of 4; true for the lanes kk = 0 at least
                 if (a.acc_in) s += *(const f4*)(a.acc_in + o);
-#ifdef WS_NT
-                __builtin_nontemporal_store(s, (f4*)(Y + o));
-#else
-                *(f4*)(Y + o) = s;
-#endif
+                stream_store((f4*)(Y + o), s);
             }
         }
     };
@@ -489,12 +485,9 @@ static int ws_nt(int k) { const int nt = (k + 15) / 16; return nt + (nt & 1); } 
 
 // LDS: nbuf tiles of 16 padded rows, and mu
 static size_t ws_lds(int d, int nbuf) { return sizeof(float) * ((size_t)nbuf * 16 * (d + WS_ROWPAD) + d); }
-// Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two; two also at d = 512, where
-// they measure 3 % faster (at d = 256 two are 20 % slower, at d = 768 2 % slower)
-#ifndef WS_NBUF
-#define WS_NBUF 3
-#endif
-static int ws_nbuf(int d) { return WS_NBUF == 3 && ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
+// Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two (with two, d = 256 is 20 %
+// slower, d = 768 2 %; d = 512 measures 3 % faster, within what one box differs from the next)
+static int ws_nbuf(int d) { return ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
 
 // One basis, d in {256, 512, 768, 1024}, k a multiple of 4, U fits the registers of 8 waves (d/256 x NT words of
 // 8 registers, at most 18), and a wave's partial result fits its strip of the tile (16 floats per column tile,
@@ -559,11 +552,9 @@ static int64_t ws_tiles(const gvq_basis* h, int64_t first_slice, int64_t n_slice
 template <auto KERN>
 static int launch_ws(const gvq_basis* h, const WsArgs& a, size_t lds, int nbuf, hipStream_t st)
 {
-    static size_t allowed = 0;   // per kernel: the largest dynamic LDS size asked for so far
-    if (lds > allowed) {
-        GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        allowed = lds;
-    }
+    static gvq_once_per_device once;   // per kernel
+    if (once.first(h->device))
+        GVQ_HIP(hipFuncSetAttribute((const void*)KERN, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
     if (grid < 1) grid = 1;   // only the slices after the last whole tile
     hipLaunchKernelGGL(KERN, dim3((unsigned)grid), dim3(512), lds, st, a, nbuf);
@@ -625,12 +616,10 @@ static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
     constexpr int D = 256 * STEPS;
     constexpr size_t lds = sizeof(float) * (2 * 16 * (D + WS_ROWPAD) + WSD_NY * 4 * 64 * ((16 * (8 * NKS + 1) + 63) / 64) + D);
     static_assert(lds <= 160 * 1024, "LDS");
-    static bool allowed = false;
-    if (!allowed) {
+    static gvq_once_per_device once;
+    if (once.first(h->device))
         GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS, EXACT>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        allowed = true;
-    }
     int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS, EXACT>), dim3((unsigned)grid), dim3(512), lds, st, a);

@@ -481,11 +481,10 @@ int gvq_launch_eigen_block(gvq_basis* h, hipStream_t st)
     if (a.cgroups > n / 8) a.cgroups = n / 8;
     if (a.cgroups < 1) a.cgroups = 1;
     const size_t lds = sizeof(double) * 2 * BJ_M * BJ_LD + 2048;   // either step's matrices, the rotation parameters
-    static bool attr_set = false;
-    if (!attr_set) {
+    static gvq_once_per_device once;
+    if (once.first(h->device)) {
         GVQ_HIP(hipFuncSetAttribute((const void*)bj_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         GVQ_HIP(hipFuncSetAttribute((const void*)bj_round_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
     }
     hipLaunchKernelGGL(bj_init_kernel, dim3(n >= 512 ? 256 : 32, h->B), dim3(256), 0, st, a);
     GVQ_HIP(hipGetLastError());

@@ -910,12 +910,10 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
         g.bf16 = h->dtype == GVQ_BF16 ? 1 : 0;
         g.cov = h->d_cov; g.work = h->d_V; g.work_stride = (size_t)(d + (d & 1)) * (d + (d & 1));
         g.eig = h->d_eig; g.U = h->d_U; g.mu = h->d_mu; g.sweeps = h->d_sweeps; g.max_sweeps = 60; g.tol = 1e-15;
-        static bool gram_attr_set = false;
-        if (!gram_attr_set) {
+        static gvq_once_per_device gram_once;
+        if (gram_once.first(h->device))
             GVQ_HIP(hipFuncSetAttribute((const void*)gram_eigen_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)gvq_gram_lds_bytes(GVQ_GRAM_MAX_L, GVQ_GRAM_MAX_K)));
-            gram_attr_set = true;
-        }
         hipLaunchKernelGGL(gram_eigen_kernel, dim3(h->B), dim3(1024), gvq_gram_lds_bytes(L, h->k), st, g);
         GVQ_HIP(hipGetLastError());
         return gvq_launch_pack(h, st);
@@ -929,12 +927,10 @@ int gvq_launch_fit(gvq_basis* h, const void* const* grads, int L, bool first_sli
     e.cov = h->d_cov; e.V = h->d_V; e.eig = h->d_eig; e.U = h->d_U; e.mu = h->d_mu;
     e.sweeps = h->d_sweeps; e.max_sweeps = 60; e.tol = 1e-15;
     const size_t lds = gvq_eigen_lds_bytes(d);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static gvq_once_per_device once;
+    if (once.first(h->device))
         GVQ_HIP(hipFuncSetAttribute((const void*)eigen_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)gvq_eigen_lds_bytes(GVQ_LDS_EIGEN_MAX_D)));
-        attr_set = true;
-    }
     const int threads = d > 16 ? 256 : 64;
     hipLaunchKernelGGL(eigen_kernel, dim3(h->B), dim3(threads), lds, st, e);
     GVQ_HIP(hipGetLastError());

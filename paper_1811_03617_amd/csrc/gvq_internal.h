@@ -82,6 +82,19 @@ int gvq_hip_fail(hipError_t e, const char* what);
 
 // Workgroups per compute unit for the streaming kernels (0 = pick from occupancy).
 int gvq_opt_wg_per_cu();
+// hipFuncSetAttribute acts on the current device: a launcher keeps one of these per kernel and raises the kernel's
+// dynamic LDS limit the first time it runs on each device (devices 0 .. 63; not synchronised, like the launch options).
+struct gvq_once_per_device {
+    unsigned long long done = 0;
+    bool first(int device)
+    {
+        const unsigned long long bit = 1ull << (device & 63);
+        if (done & bit) return false;
+        done |= bit;
+        return true;
+    }
+};
+
 // Tiles per run in the MFMA kernels' schedule (0 = default).
 int gvq_opt_run_tiles();
 // LDS-tiled codec kernels: 0 = pick the matrix pipe from the shape, 1 = fp32 products, 2 = the bf16 split,
