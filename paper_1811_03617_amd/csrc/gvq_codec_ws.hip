@@ -52,6 +52,14 @@ __device__ __forceinline__ void copy_1k_to_lds(const void* src_lane, unsigned in
                  : "memory", "m0");
 }
 
+// 128 bits global -> registers that the compiler does not count either (it would wait for every copy in flight before
+// the first use): the caller waits by hand and then passes the value through claim_loaded before using it.
+__device__ __forceinline__ void load_uncounted(f4& v, const float* p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=&v"(v) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void claim_loaded(f4& v) { asm volatile("" : "+v"(v)); }
+
 // --------------------------------------------------------------------------------------
 // compress.  LDS: xs[2][16][d + 4] floats, part[8][NT][64] 128-bit words, mus[d] floats.
 // --------------------------------------------------------------------------------------
@@ -88,6 +96,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
 
     // Wave v adds up column tile v when that tile holds a comp below k; it then issues exactly one store per tile.
     const bool adds = 16 * w < a.k;
+    const bool ring = a.acc_in != nullptr;
     // nbuf - 1 tiles are in flight while one is worked on
     const int ahead = nbuf - 1;
     int64_t t = blockIdx.x;
@@ -104,6 +113,12 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
     // AHEAD: the pieces of tile `ta` are copied into buffer `bufa` between the products.
     auto work_tile = [&](auto ahead_c, int buf, int64_t tile, int rows, int64_t ta, int bufa) {
         constexpr bool AHEAD = decltype(ahead_c)::value;
+        // ring step: this lane's word of the partial sum, asked for before the tile's copies and used after them
+        f4 prev = {0.f, 0.f, 0.f, 0.f};
+        if (adds && ring) {
+            const int rr = n_ < rows ? n_ : rows - 1, cc = 16 * w + 4 * kk < a.k ? 16 * w + 4 * kk : a.k - 4;
+            load_uncounted(prev, a.acc_in + (a.first + 16 * tile + rr) * a.k + cc);
+        }
         f4 acc[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
@@ -160,10 +175,13 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
             const int c0 = 16 * w + 4 * kk;
             const int64_t o = (a.first + 16 * tile + n_) * a.k + c0;
             float* Y = (float*)a.out;
-            if (c0 < a.k && n_ < rows) {   // k is a multiple of 4; true for the lanes kk = 0 at least
-                if (a.acc_in) s += *(const f4*)(a.acc_in + o);
-                stream_store((f4*)(Y + o), s);
+            if (ring) {
+                // younger than the word asked for: this tile's copies
+                if constexpr (AHEAD) wait_vmem_at_most<2 * STEPS>(); else wait_vmem_at_most<0>();
+                claim_loaded(prev);
+                s += prev;
             }
+            if (c0 < a.k && n_ < rows) stream_store((f4*)(Y + o), s);   // k is a multiple of 4; true for kk = 0 at least
         }
     };
 
@@ -176,7 +194,9 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
         // than them are the copies of the tiles between (2 STEPS each) and one store per tile for the waves
         // that add up a column tile.
         if (ahead == 2) {
-            if (adds) wait_vmem_at_most<2 * STEPS + 2>(); else wait_vmem_at_most<2 * STEPS>();
+            if (adds && ring) wait_vmem_at_most<2 * STEPS + 3>();   // ... and the word of the partial sum in between
+            else if (adds) wait_vmem_at_most<2 * STEPS + 2>();
+            else wait_vmem_at_most<2 * STEPS>();
         } else {
             if (adds) wait_vmem_at_most<1>(); else wait_vmem_at_most<0>();
         }
