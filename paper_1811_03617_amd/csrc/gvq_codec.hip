@@ -49,7 +49,9 @@ __device__ __forceinline__ int super_basis(const CodecArgs& a, int64_t p)
 
 // NSO = 128-bit result words per lane and super-tile: ceil(8 k / D), a template value so that the
 // stores can be counted (YS picks it: the largest possible number, G * NT, shifted right by YS).
-template <int D, int NT, bool BF16, int VAR, int YS, bool MANY>
+// LOSS: Eq. (6) instead of Eq. (2): the per-slice squared residual is written (a.out: one float per slice), see the
+// general phase of the kernel for how the reconstruction comes out of the accumulators; a.il must be 1.
+template <int D, int NT, bool BF16, int VAR, int YS, bool MANY, bool LOSS = false>
 __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
 {
     constexpr int G = 128 / D;                    // 16-slice tiles per super-tile
@@ -89,6 +91,7 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
     }
 
     f4 uf[NQ][NT];
+    f4 ud[LOSS ? NQ : 1][NT];   // LOSS only: ud[et][q][j] = U[16et + n_][16q + 4kk + j]
     float mun[EPL];
     auto load_basis = [&](int b) {
         const f4* Up = a.Upack + (size_t)b * (NQ * NT * 64) + lane;
@@ -97,6 +100,13 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
         for (int q = 0; q < NQ; ++q)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) uf[q][nt] = Up[(q * NT + nt) * 64];
+        if constexpr (LOSS) {
+            const f4* Up2 = a.Upack2 + (size_t)b * (NQ * NT * 64) + lane;
+#pragma unroll
+            for (int et = 0; et < NQ; ++et)
+#pragma unroll
+                for (int q = 0; q < NT; ++q) ud[et][q] = Up2[(et * NT + q) * 64];
+        }
 #pragma unroll
         for (int i = 0; i < EPL; ++i) mun[i] = mub[lc * EPL + i] / a.n_workers;
     };
@@ -203,6 +213,32 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
                     for (int nt = 0; nt < NT; ++nt)
                         acc[g][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(uf[q][nt][j], x[g][q][j], acc[g][nt], 0, 0, 0);
             });
+            if constexpr (LOSS) {
+                // whole slices inside the gradient: every element counts
+                const int64_t s0 = super_tile<G, MANY>(a, cur) * TILE_SLICES;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float sq = 0.f;
+#pragma unroll
+                    for (int et = 0; et < NQ; ++et) {
+                        f4 rec = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int q = 0; q < NT; ++q)
+#pragma unroll
+                            for (int jj = 0; jj < 4; ++jj)
+                                rec = __builtin_amdgcn_mfma_f32_16x16x4f32(ud[et][q][jj], acc[g][q][jj], rec, 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float df = x[g][et][r] - rec[r];
+                            sq = fmaf(df, df, sq);
+                        }
+                    }
+                    sq += __shfl_xor(sq, 16, 64);
+                    sq += __shfl_xor(sq, 32, 64);
+                    if (kk == 0) ((float*)a.out)[s0 + g * 16 + n_] = sq;
+                }
+                __builtin_amdgcn_s_setprio(0);
+            } else {
             __builtin_amdgcn_s_setprio(0);
             if (a.pace & 2) drain_memory();
             // the result tiles leave through the same LDS region (every x is in registers by now) as
@@ -220,6 +256,7 @@ __device__ __forceinline__ void compress_fast_phase(const CodecArgs& a, f4* lds)
                 f4 v = lds[so_slot[r]];
                 if constexpr (RING) v += pv[r];
                 stream_store((f4*)(o + 4 * so_row[r] * wc.rstride * orw + so_in[r]), v);
+            }
             }
             cur = nxt;
             wc = wn;
@@ -262,10 +299,8 @@ __global__ __launch_bounds__(WG_THREADS, LOSS ? 1 : 2) void compress_mfma_kernel
     f4* lds = lds_all[threadIdx.x >> 6];
     f4* ldso = ldso_all[threadIdx.x >> 6];
 
-    if constexpr (!LOSS) {
-        if (a.sup_tile) compress_fast_phase<D, NT, BF16, VAR, YS, true>(a, lds);
-        else compress_fast_phase<D, NT, BF16, VAR, YS, false>(a, lds);
-    }
+    if (a.sup_tile) compress_fast_phase<D, NT, BF16, VAR, YS, true, LOSS>(a, lds);
+    else compress_fast_phase<D, NT, BF16, VAR, YS, false, LOSS>(a, lds);
 
     // ---- general phase: the tiles the fast phase leaves out, every check in place ----------
     RestIter it;
@@ -1850,9 +1885,11 @@ static int launch_loss_t(const gvq_basis* h, const CodecArgs& a, hipStream_t st)
 {
     constexpr auto kern = compress_mfma_kernel<D, NT, BF16, 0, true, 0>;
     CodecArgs b = a;
-    plan_tiles(h, b, 128 / D, false, 0);   // the residual kernel has no fast phase: every tile is a rest tile
+    plan_tiles(h, b, 128 / D, (h->k & 3) == 0 && !(gvq_opt_no_fast() & 1), 0);
     int grid = streaming_grid<kern>(h, work_items(b));
-    b.run_tiles = 1;
+    b.run_tiles = run_length(h, b.n_super, grid);
+    b.rest_run = run_length(h, work_items(b) - b.n_super, grid);
+    b.il = 1;   // the per-slice results are addressed by slice: no row interleave
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
