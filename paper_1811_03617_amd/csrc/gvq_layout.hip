@@ -62,49 +62,54 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_kernel(LayoutArgs 
     }
 }
 
-// fp32, 16-byte aligned sides, F and D*H*W multiples of 4: the same tile scheme with 128-bit global accesses and no
-// division per element.  LDS holds the tile in the flat order, tile[g][f], g = hw * nd + dd the position inside the
-// tile and f fastest (row stride TF + 4 floats: 128-bit rows, and 8 lanes x 128 bits cover all banks).  On the
-// [F][D][H][W] side a thread moves 4 consecutive numbers of one filter's run (and scatters them to, or gathers them
-// from, 4 rows of the tile); on the flat side a thread moves 4 adjacent filters of one row.
-#define LF_WORDS 8192           // floats of LDS per work-group (32 KB)
+// 16-byte aligned sides, F and D*H*W multiples of V = 16 / sizeof(T) (4 for fp32, 8 for bf16): the same tile scheme
+// with 128-bit global accesses and no division per element.  LDS holds the tile in the flat order, tile[g][f],
+// g = hw * nd + dd the position inside the tile and f fastest (row stride TF + V elements: 128-bit rows, and 8 lanes x
+// 128 bits cover all banks).  On the [F][D][H][W] side a thread moves V consecutive numbers of one filter's run (and
+// scatters them to, or gathers them from, V rows of the tile); on the flat side a thread moves V adjacent filters of
+// one row.
+#define LF_BYTES 32768          // LDS per work-group
 
 struct LayoutFastArgs {
-    const float* src;
-    float* dst;
-    int F, D, HW, TD;           // TD * HW is a multiple of 4 and at most LF_WORDS / (TF + 4)
+    const void* src;
+    void* dst;
+    int F, D, HW, TD;           // TD * HW is a multiple of V and at most LF_BYTES / sizeof(T) / (TF + V)
     int n_dtiles;
 };
 
-// TF: filters per tile (a row of the flat side is TF * 4 bytes contiguous)
-template <bool FLATTEN, int TF>
+typedef unsigned int lu4 __attribute__((ext_vector_type(4)));
+
+// TF: filters per tile (a row of the flat side is TF elements contiguous)
+template <typename T, bool FLATTEN, int TF>
 __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_fast_kernel(LayoutFastArgs a)
 {
-    extern __shared__ float ftile[];   // [run][RS]
-    constexpr int RS = TF + 4, QF = TF / 4, ROWS = LAYOUT_THREADS / QF;   // row stride, threads per row, rows per pass
+    extern __shared__ lu4 ftile_raw[];
+    T* ftile = (T*)ftile_raw;   // [run][RS]
+    constexpr int V = 16 / sizeof(T), RS = TF + V, QF = TF / V, ROWS = LAYOUT_THREADS / QF;
+    union Vec { lu4 v; T e[V]; };
     const int tid = threadIdx.x;
     const int ft = blockIdx.x / a.n_dtiles, dt = blockIdx.x % a.n_dtiles;
     const int f0 = ft * TF, d0 = dt * a.TD;
-    const int nf = a.F - f0 < TF ? a.F - f0 : TF;             // a multiple of 4
+    const int nf = a.F - f0 < TF ? a.F - f0 : TF;             // a multiple of V
     const int nd = a.D - d0 < a.TD ? a.D - d0 : a.TD;
-    const int run = nd * a.HW, rq = run >> 2;                // run: a multiple of 4, at most LF_WORDS / RS
-    const float* grad = FLATTEN ? a.src : a.dst;
-    const float* flat = FLATTEN ? a.dst : a.src;
+    const int run = nd * a.HW, rq = run / V;                 // run: a multiple of V, rq <= 32
+    const T* grad = (const T*)(FLATTEN ? a.src : a.dst);
+    const T* flat = (const T*)(FLATTEN ? a.dst : a.src);
     // the [F][D][H][W] side: this thread's chunk c of a run, for filters fsub, fsub + fpp, ...
     const int fpp = LAYOUT_THREADS / rq, fsub = tid / rq, c = tid - fsub * rq;
-    int g[4];
+    int g[V];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = 4 * c + i, dd = r / a.HW, hw = r - dd * a.HW;
+    for (int i = 0; i < V; ++i) {
+        const int r = V * c + i, dd = r / a.HW, hw = r - dd * a.HW;
         g[i] = (hw * nd + dd) * RS;
     }
-    // the flat side: 4 adjacent filters q of rows gr, gr + ROWS, ...
+    // the flat side: V adjacent filters q of rows gr, gr + ROWS, ...
     const int q = tid % QF, gr = tid / QF;
-    auto grad_ptr = [&](int f) { return (float*)grad + ((size_t)(f0 + f) * a.D + d0) * a.HW + 4 * c; };
+    auto grad_ptr = [&](int f) { return (T*)grad + ((size_t)(f0 + f) * a.D + d0) * a.HW + V * c; };
     auto flat_rows = [&](auto&& body) {
         int hw = gr / nd, dd = gr - hw * nd;
         for (int gg = gr; gg < run; gg += ROWS) {
-            if (4 * q < nf) body(gg, (float*)flat + ((size_t)hw * a.D + d0 + dd) * a.F + f0 + 4 * q);
+            if (V * q < nf) body(gg, (T*)flat + ((size_t)hw * a.D + d0 + dd) * a.F + f0 + V * q);
             dd += ROWS;
             while (dd >= nd) { dd -= nd; ++hw; }
         }
@@ -112,52 +117,48 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_fast_kernel(Layout
     if (FLATTEN) {
         if (fsub < fpp)
             for (int f = fsub; f < nf; f += fpp) {
-                const f4 v = __builtin_nontemporal_load((const f4*)grad_ptr(f));
+                Vec x;
+                x.v = __builtin_nontemporal_load((const lu4*)grad_ptr(f));
 #pragma unroll
-                for (int i = 0; i < 4; ++i) ftile[g[i] + f] = v[i];
+                for (int i = 0; i < V; ++i) ftile[g[i] + f] = x.e[i];
             }
         __syncthreads();
-        flat_rows([&](int gg, float* p) { __builtin_nontemporal_store(*(const f4*)(ftile + gg * RS + 4 * q), (f4*)p); });
+        flat_rows([&](int gg, T* p) { __builtin_nontemporal_store(*(const lu4*)(ftile + gg * RS + V * q), (lu4*)p); });
     } else {
-        flat_rows([&](int gg, float* p) { *(f4*)(ftile + gg * RS + 4 * q) = __builtin_nontemporal_load((const f4*)p); });
+        flat_rows([&](int gg, T* p) { *(lu4*)(ftile + gg * RS + V * q) = __builtin_nontemporal_load((const lu4*)p); });
         __syncthreads();
         if (fsub < fpp)
             for (int f = fsub; f < nf; f += fpp) {
-                f4 v;
+                Vec x;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = ftile[g[i] + f];
-                __builtin_nontemporal_store(v, (f4*)grad_ptr(f));
+                for (int i = 0; i < V; ++i) x.e[i] = ftile[g[i] + f];
+                __builtin_nontemporal_store(x.v, (lu4*)grad_ptr(f));
             }
     }
 }
 
 // Depths per tile for the kernel above with at most max_run rows, or 0 when the shape does not fit it.
-static int layout_fast_td(const void* src, const void* dst, int F, int D, int HW, int max_run)
+static int layout_fast_td(const void* src, const void* dst, int F, int D, int HW, int V, int max_run)
 {
-    if ((((uintptr_t)src | (uintptr_t)dst) & 15) || (F & 3) || (((int64_t)D * HW) & 3) || HW > max_run) return 0;
-    const int step = (HW & 3) == 0 ? 1 : (HW & 1) == 0 ? 2 : 4;   // TD * HW must be a multiple of 4
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15) || F % V || ((int64_t)D * HW) % V || HW > max_run) return 0;
+    int step = V;                                  // TD * HW must be a multiple of V: TD of V / gcd(HW, V)
+    while (step > 1 && (HW * (step / 2)) % V == 0) step /= 2;
     int td = max_run / HW / step * step;
     if (td < step) return 0;
-    if (td >= D) return D;                                        // one depth tile: D * HW is a multiple of 4
+    if (td >= D) return D;                         // one depth tile: D * HW is a multiple of V
     return td;
 }
 
-template <bool FLATTEN, int TF>
+template <typename T, bool FLATTEN, int TF>
 static int launch_layout_fast(const void* src, void* dst, int F, int D, int HW, int td, hipStream_t st)
 {
     LayoutFastArgs a;
-    a.src = (const float*)src; a.dst = (float*)dst; a.F = F; a.D = D; a.HW = HW; a.TD = td;
+    a.src = src; a.dst = dst; a.F = F; a.D = D; a.HW = HW; a.TD = td;
     a.n_dtiles = (D + td - 1) / td;
     const int n_ftiles = (F + TF - 1) / TF;
-    const size_t lds = sizeof(float) * (size_t)td * HW * (TF + 4);
-    static gvq_once_per_device once;
-    int dev = 0;
-    GVQ_HIP(hipGetDevice(&dev));
-    if (once.first(dev))
-        GVQ_HIP(hipFuncSetAttribute((const void*)conv_layout_fast_kernel<FLATTEN, TF>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, LF_WORDS * 4));
-    hipLaunchKernelGGL((conv_layout_fast_kernel<FLATTEN, TF>), dim3(n_ftiles * a.n_dtiles), dim3(LAYOUT_THREADS), lds, st,
-                       a);
+    const size_t lds = sizeof(T) * (size_t)td * HW * (TF + 16 / sizeof(T));
+    hipLaunchKernelGGL((conv_layout_fast_kernel<T, FLATTEN, TF>), dim3(n_ftiles * a.n_dtiles), dim3(LAYOUT_THREADS), lds,
+                       st, a);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
@@ -179,14 +180,15 @@ __global__ void conv_layout_direct_kernel(const T* src, T* dst, int F, int D, in
 template <typename T, bool FLATTEN>
 static int launch_layout(const void* src, void* dst, int F, int D, int HW, hipStream_t st)
 {
-    if constexpr (sizeof(T) == 4) {
-        // 64 filters per tile (256-byte rows on the flat side); 128 when a fully connected layer is flattened (measured
-        // on 67 - 411 MB layers: 4.2 - 4.6 against 3.9 TB/s; with H*W > 1, and for unflatten, 128 is 15 - 30 % slower)
-        const int tf = FLATTEN && HW == 1 && F >= 128 ? 128 : 64;
-        const int td = layout_fast_td(src, dst, F, D, HW, (LF_WORDS / (tf + 4)) & ~3);
+    {
+        // 64 filters per tile; 128 when a fully connected fp32 layer is flattened (measured on 67 - 411 MB layers:
+        // 4.2 - 4.6 against 3.9 TB/s; with H*W > 1, and for unflatten, 128 is 15 - 30 % slower)
+        constexpr int V = 16 / sizeof(T);
+        const int tf = sizeof(T) == 4 && FLATTEN && HW == 1 && F >= 128 ? 128 : 64;
+        const int td = layout_fast_td(src, dst, F, D, HW, V, LF_BYTES / (int)sizeof(T) / (tf + V) / V * V);
         if (td > 0) {
-            if (tf == 128) return launch_layout_fast<FLATTEN, 128>(src, dst, F, D, HW, td, st);
-            return launch_layout_fast<FLATTEN, 64>(src, dst, F, D, HW, td, st);
+            if (tf == 128) return launch_layout_fast<T, FLATTEN, 128>(src, dst, F, D, HW, td, st);
+            return launch_layout_fast<T, FLATTEN, 64>(src, dst, F, D, HW, td, st);
         }
     }
     if ((int64_t)LAYOUT_TF * HW > LAYOUT_LDS_ELEMS) {

@@ -18,9 +18,10 @@ SHAPES = [
     (32, 20, 5, 5), (64, 3, 7, 7),
     (8, 2, 13, 13),      # H*W too large for a tile: direct kernel
     (512, 512, 3, 3),    # 2.4 M numbers
-    # the 128-bit path (fp32, F and D*H*W multiples of 4): ragged filter tile, ragged depth tile, one depth tile,
+    # the 128-bit path (F and D*H*W multiples of 4 for fp32, of 8 for bf16): ragged filter tile, ragged depth tile, one depth tile,
     # a fully connected layer (a plain transpose), H*W = 49 with 4 depths per tile, F below one tile
     (68, 36, 3, 3), (64, 28, 5, 5), (128, 4, 3, 3), (1000, 4096, 1, 1), (128, 8, 7, 7), (4, 240, 1, 1), (8, 484, 1, 1),
+    (72, 40, 5, 5), (200, 24, 3, 3), (8, 16, 2, 2),   # ... and multiples of 8 for bf16
 ]
 
 
