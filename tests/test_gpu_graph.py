@@ -15,7 +15,9 @@ DEV = "cuda:0"
 @pytest.mark.parametrize("M,d,k,N,dtype,block_elems", [
     (128 * 3000 + 40, 128, 32, 4, "f32", 0),            # register-resident kernels
     (128 * 2000 + 40, 128, 16, 3, "bf16", 128 * 300),   # bf16 pipe, several bases
-    (768 * 300 + 9, 768, 96, 2, "f32", 0),              # LDS-tiled kernels, bf16-split products
+    (768 * 300 + 9, 768, 96, 2, "f32", 0),              # basis-stationary kernels, bf16-split products
+    (1024 * 200 + 5, 1024, 16, 2, "f32", 0),            # basis-stationary kernels, exact fp32 products
+    (768 * 300 + 9, 768, 96, 2, "bf16", 0),             # LDS-tiled kernels
 ])
 def test_graph_replays_match_eager_calls(M, d, k, N, dtype, block_elems):
     w = Workload("t", M, d, k, N, 2, dtype, 4, 0.1, block_elems=block_elems, seed=31)
