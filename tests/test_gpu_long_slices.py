@@ -156,9 +156,9 @@ def test_fit_at_the_largest_slice_length_by_invariants():
     assert max_angle(Ub[:, :8], V_ref[:, ::-1][:, :8]) < ANGLE_TOL         # the planted directions
 
 
-def _check_codec(w, out_dtype=None):
+def _check_codec(w, out_dtype=None, fit=True):
     rng = np.random.default_rng(w.seed)
-    if w.M // w.d >= 2 * w.d:      # enough samples for a meaningful fit
+    if fit and w.M // w.d >= 2 * w.d:      # enough samples for a meaningful fit
         fitg = [synth.to_numpy(g) for g in synth.fit_gradients(w, "cpu")]
         U, mu, _ = oracle.fit(fitg, w.d, w.k, dtype=w.dtype, offsets=w.block_offsets())
     else:
@@ -239,7 +239,7 @@ def test_codec_and_loss_parity(M, d, k, N, dtype, block_elems, pipe):
     (768 * 31 + 767, 768, 96, 2),   # a tail of 16 slices, the last one element short
     (768 * 32, 768, 96, 2),         # whole tiles only
     (1024 * 47 + 2, 1024, 64, 2),   # two buffers in LDS instead of three
-    (768 * 4113 + 700, 768, 96, 2), # more tiles than work-groups, several per work-group
+    (768 * 4113 + 700, 768, 96, 2), # more tiles than work-groups
 ])
 def test_basis_stationary_kernels(M, d, k, N):
     """fp32 gradients, one basis, d a multiple of 256, the bf16-split pipe: compress, and decompress into fp32, keep U
@@ -251,6 +251,19 @@ def test_basis_stationary_kernels(M, d, k, N):
             _check_codec(_wl(M, d, k, N, 2), out_dtype=out_dtype)
         finally:
             gvq.lib().gvq_set_option(2, 0)
+
+
+@pytest.mark.parametrize("M,d,k", [
+    (768 * (16 * 256 * 6 + 37) + 100, 768, 96),
+    (768 * (16 * 256 * 5 + 3), 768, 16),            # exact products by default
+    (1024 * (16 * 256 * 5 + 5), 1024, 64),          # two buffers in LDS
+    (256 * (16 * 256 * 6 + 9) + 3, 256, 32),
+])
+def test_basis_stationary_kernels_with_several_tiles_per_work_group(M, d, k):
+    """Five or six tiles per work-group on the whole chip: every ring of LDS buffers wraps around, and whole groups of
+    16 interleaved tiles, the tiles after the last whole group and the tail tile all occur.  With a random orthonormal
+    basis: an oracle fit of this size would take minutes and is not what this test is about."""
+    _check_codec(_wl(M, d, k, 1, 2), fit=False)
 
 
 def test_pipe_option_range():
