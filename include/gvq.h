@@ -248,14 +248,14 @@ const char* gvq_strerror(int status);
  *   option 0: workgroups per compute unit for the streaming kernels;
  *   option 1: consecutive 16-slice tiles a wave takes before it jumps ahead by the width
  *             of the whole grid (1 = interleave single tiles, large = one chunk per wave);
- *   option 2: matrix pipe of the LDS-tiled codec kernels (slices longer than 128 elements, and
+ *   option 2: matrix pipe of the long-slice codec kernels (slices longer than 128 elements, and
  *             shorter shapes other than d in {16,32,64,128} with k <= 32): 0 = exact fp32
  *             products where they keep up with memory (2dk/(4(d+k)) < 10 flop per byte),
  *             else products of two-term bf16 splits with fp32 accumulation (each product good to
  *             about 1e-5 of its magnitude, results within 1e-5 of the exact ones relative to the
  *             largest value, up to 2 times faster); 1 = always exact products; 2 = always the split;
- *             3 = always the split, and compress never takes the kernel that keeps U in registers
- *             (its default for fp32 gradients with one basis and d a multiple of 256, for A/B timing);
+ *             3 = always the split, and never the kernels that keep U in registers (the default
+ *             for fp32 gradients with one basis and d a multiple of 256; for A/B timing);
  *   option 3: bit mask that sends every tile of a kernel family through its bounds-checked general loop
  *             instead of the branch-free loop over whole tiles (1: fp32-pipe compress, 2: bf16-pipe
  *             compress, 4: decompress); results are identical, for A/B timing;
