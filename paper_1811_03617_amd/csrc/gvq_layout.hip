@@ -181,10 +181,11 @@ template <typename T, bool FLATTEN>
 static int launch_layout(const void* src, void* dst, int F, int D, int HW, hipStream_t st)
 {
     {
-        // 64 filters per tile; 128 when a fully connected fp32 layer is flattened (measured on 67 - 411 MB layers:
-        // 4.2 - 4.6 against 3.9 TB/s; with H*W > 1, and for unflatten, 128 is 15 - 30 % slower)
+        // 64 filters per tile; 128 for a fully connected layer when it is flattened or holds bf16 (measured on 67 - 411 MB
+        // layers: fp32 flatten 4.2 - 4.6 against 3.9 TB/s, bf16 3.5 / 3.2 against 2.7 / 2.6; with H*W > 1, and for the
+        // fp32 unflatten, 128 is 15 - 30 % slower)
         constexpr int V = 16 / sizeof(T);
-        const int tf = sizeof(T) == 4 && FLATTEN && HW == 1 && F >= 128 ? 128 : 64;
+        const int tf = HW == 1 && F >= 128 && (FLATTEN || sizeof(T) == 2) ? 128 : 64;
         const int td = layout_fast_td(src, dst, F, D, HW, V, LF_BYTES / (int)sizeof(T) / (tf + V) / V * V);
         if (td > 0) {
             if (tf == 128) return launch_layout_fast<T, FLATTEN, 128>(src, dst, F, D, HW, td, st);
