@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--skip-fit", action="store_true",
                     help="import a seeded random orthonormal basis instead of fitting one (counter runs: the "
                          "long-slice fit enqueues tens of thousands of small kernels)")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="leave out the timings of the ring step, the monitor and flatten (profiler runs: their "
+                         "launches would mix with those of the timed steps in per-kernel statistics)")
     ap.add_argument("--option", action="append", default=[], metavar="INDEX=VALUE",
                     help="gvq_set_option(INDEX, VALUE) before the run (launch tuning, for A/B timings); repeatable")
     args = ap.parse_args()
@@ -165,6 +168,8 @@ def run_workload(name, args):
         torch.cuda.synchronize()
 
     # ---- the rows beyond Eqs. 2-4, each timed on its own (not part of `value`) -------------------------------
+    next_rows = None
+
     def per_call_ms(fn, n=10):
         fn(); fn()
         a0, a1 = ev(), ev()
@@ -175,21 +180,28 @@ def run_workload(name, args):
         torch.cuda.synchronize()
         return a0.elapsed_time(a1) / n
 
-    # Algorithm 1's ring step: compress a worker's gradient and add the partial sum that came in (fused)
-    ring_ms = per_call_ms(lambda i=0: basis.compress_segment(workers[i % w.N], w.N, 0, S, comps[(i + 1) % 2], comps[i % 2]))
-    # Eq. 6 monitor: per-basis squared residual of one gradient (three launches)
-    loss_dev = torch.empty(w.n_blocks, device=dev, dtype=torch.float64)
-    loss_ms = per_call_ms(lambda i=0: basis.local_loss(workers[i % w.N], w.N, loss_dev))
-    # Fig. 2a flattening of the largest layer of this size class: a fully connected layer, [F][D][1][1]
-    lay_F = 4096 if w.M >= 4096 * 4096 else 64
-    lay_D = min(w.M, 1 << 26) // lay_F
-    lay = workers[0][:lay_F * lay_D]
-    flat_dev = torch.empty_like(lay)
-    code = gvq.BF16 if w.dtype == "bf16" else gvq.F32
-    flat_ms = per_call_ms(lambda i=0: gvq.gvq_flatten_conv(lay, flat_dev, lay_F, lay_D, 1, 1, code))
-    unflat_ms = per_call_ms(lambda i=0: gvq.gvq_unflatten_conv(flat_dev, out[:lay_F * lay_D], lay_F, lay_D, 1, 1, code))
-    step()   # leaves comps / total / out as the timed steps did
-    torch.cuda.synchronize()
+    if not args.no_next_rows:
+        # Algorithm 1's ring step: compress a worker's gradient and add the partial sum that came in (fused)
+        ring_ms = per_call_ms(lambda i=0: basis.compress_segment(workers[i % w.N], w.N, 0, S, comps[(i + 1) % 2], comps[i % 2]))
+        # Eq. 6 monitor: per-basis squared residual of one gradient (three launches)
+        loss_dev = torch.empty(w.n_blocks, device=dev, dtype=torch.float64)
+        loss_ms = per_call_ms(lambda i=0: basis.local_loss(workers[i % w.N], w.N, loss_dev))
+        # Fig. 2a flattening of the largest layer of this size class: a fully connected layer, [F][D][1][1]
+        lay_F = 4096 if w.M >= 4096 * 4096 else 64
+        lay_D = min(w.M, 1 << 26) // lay_F
+        lay = workers[0][:lay_F * lay_D]
+        flat_dev = torch.empty_like(lay)
+        code = gvq.BF16 if w.dtype == "bf16" else gvq.F32
+        flat_ms = per_call_ms(lambda i=0: gvq.gvq_flatten_conv(lay, flat_dev, lay_F, lay_D, 1, 1, code))
+        unflat_ms = per_call_ms(lambda i=0: gvq.gvq_unflatten_conv(flat_dev, out[:lay_F * lay_D], lay_F, lay_D, 1, 1, code))
+        next_rows = {"ring_step_ms": round(ring_ms, 4),
+                     "ring_step_GBs": round((comp_bytes + S * 4 * w.k) / ring_ms / 1e6, 1),
+                     "local_loss_ms": round(loss_ms, 4), "local_loss_gradient_GBs": round(w.M * es / loss_ms / 1e6, 1),
+                     "flatten_layer": f"[{lay_F}][{lay_D}][1][1]",
+                     "flatten_GBs": round(2 * lay_F * lay_D * es / flat_ms / 1e6, 1),
+                     "unflatten_GBs": round(2 * lay_F * lay_D * es / unflat_ms / 1e6, 1)}
+        step()   # leaves comps / total / out as the timed steps did
+        torch.cuda.synchronize()
 
     # reconstruction quality (the paper's loss ||ghat - g||^2 / ||g||^2), as a sanity number
     gsum = torch.zeros(w.M, device=dev, dtype=torch.float64)
@@ -234,12 +246,7 @@ def run_workload(name, args):
         "fit": None if args.skip_fit else {"ms": round(fit_ms, 3), "L": L, "jacobi_sweeps": sweeps,
                                             "input_GBs": round(L * w.M * es / fit_ms / 1e6, 1)},
         "reconstruction_loss": loss,
-        "next_rows": {"ring_step_ms": round(ring_ms, 4),
-                      "ring_step_GBs": round((comp_bytes + S * 4 * w.k) / ring_ms / 1e6, 1),
-                      "local_loss_ms": round(loss_ms, 4), "local_loss_gradient_GBs": round(w.M * es / loss_ms / 1e6, 1),
-                      "flatten_layer": f"[{lay_F}][{lay_D}][1][1]",
-                      "flatten_GBs": round(2 * lay_F * lay_D * es / flat_ms / 1e6, 1),
-                      "unflatten_GBs": round(2 * lay_F * lay_D * es / unflat_ms / 1e6, 1)},
+        "next_rows": next_rows,
         "roofline": {"bound": "hbm", "kernel": "compress", "achieved": round(comp_bytes / comp_ms / 1e6, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(comp_bytes / comp_ms / 1e6 / HBM_PEAK_GBS, 4),
