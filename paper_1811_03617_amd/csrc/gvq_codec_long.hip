@@ -968,11 +968,11 @@ int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t fi
                                void* out, gvq_dtype_t odt, hipStream_t st)
 {
     const bool split = gvq_long_split(h), bf = odt == GVQ_BF16;
-    // fp32 output in the shapes it takes: the kernel that keeps U in registers (option 2 = 3: never); with exact fp32
+    // the shapes it takes (one basis, d a multiple of 256): the kernel that keeps U in registers (option 2 = 3: never); with exact fp32
     // products from d = 512 up, like compress (d = 1024, k = 16: 5.2 against 3.0 TB/s, d = 512, k = 16: 5.2 against 4.5)
-    if (!bf && gvq_wsd_shape(h) && gvq_opt_long_mode() != 3 && (split || h->d >= 512)) {
+    if (gvq_wsd_shape(h) && gvq_opt_long_mode() != 3 && (split || h->d >= 512)) {
         int64_t done = 0;
-        const int rc = gvq_launch_decompress_ws(h, comp, first_slice, n_slices, (float*)out, !split, st, &done);
+        const int rc = gvq_launch_decompress_ws(h, comp, first_slice, n_slices, out, bf, !split, st, &done);
         if (rc != GVQ_OK) return rc;
         first_slice += done;
         n_slices -= done;

@@ -273,7 +273,7 @@ __global__ void pack_ws_kernel(const float* U, unsigned short* Uc, int d, int k,
 // --------------------------------------------------------------------------------------
 struct WsdArgs {
     const float* y;          // compressed gradient
-    float* out;              // gradient
+    void* out;               // gradient (fp32, or bf16 for OBF)
     const u4* Upack;         // the operand-order copy of U (layout at the pack kernel)
     const float* zero;       // 4 floats of zeros
     const float* mu;         // [d]
@@ -290,7 +290,8 @@ struct WsdArgs {
 
 // EXACT: fp32 products on v_mfma_f32_16x16x4_f32; U's words then hold floats, word [ti][ks][h], register r:
 // U[EW w + 16 ti + m][32 ks + 16 h + 4 kk + r] for lane (m, kk).
-template <int STEPS, int NKS, bool EXACT>
+// OBF: the output is bf16 (round to nearest even at the row stores, 8 numbers per lane and store).
+template <int STEPS, int NKS, bool EXACT, bool OBF>
 __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
 {
     extern __shared__ f4 smem[];
@@ -332,11 +333,21 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
         }
     };
 
-    // Rows 2w and 2w + 1 of the result tile in os[buf] leave whole, piece i = 0 .. 2 STEPS - 1 at a time.
+    // Rows 2w and 2w + 1 of the result tile in os[buf] leave whole, piece i = 0 .. NST - 1 at a time: 1 KB of output
+    // per piece, i.e. 256 fp32 or 512 bf16 numbers of the two rows taken as one run of 2 D numbers.
+    constexpr int NST = OBF ? STEPS : 2 * STEPS, PER = OBF ? 8 : 4;
     auto store_piece = [&](int buf, int64_t tile, int i) {
-        const int row = 2 * w + i / STEPS, q = i % STEPS;
-        const f4 v = *(const f4*)(os + (buf * 16 + row) * RS + q * 256 + lane * 4);
-        stream_store((f4*)(a.out + (a.first + slice_of(tile, row)) * (int64_t)D + q * 256 + lane * 4), v);
+        const int e = (256 * PER / 4) * i + PER * lane, row = 2 * w + e / D, col = e % D;
+        const float* src = os + (buf * 16 + row) * RS + col;
+        const int64_t o = (a.first + slice_of(tile, row)) * (int64_t)D + col;
+        if constexpr (OBF) {
+            const f4 v0 = *(const f4*)src, v1 = *(const f4*)(src + 4);
+            const u4 pk = {f32_to_bf16_rne(v0.x) | (f32_to_bf16_rne(v0.y) << 16), f32_to_bf16_rne(v0.z) | (f32_to_bf16_rne(v0.w) << 16),
+                           f32_to_bf16_rne(v1.x) | (f32_to_bf16_rne(v1.y) << 16), f32_to_bf16_rne(v1.z) | (f32_to_bf16_rne(v1.w) << 16)};
+            stream_store((u4*)((unsigned short*)a.out + o), pk);
+        } else {
+            stream_store((f4*)((float*)a.out + o), *(const f4*)src);
+        }
     };
     // The products of one tile out of ys[ybuf] into os[buf]; between them, when there is one, the stores of the tile
     // before (`prev`, in the other result buffer): the store unit takes them while the matrix pipe works, instead of
@@ -378,8 +389,8 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
             }
             if (have_prev) {
 #pragma unroll
-                for (int i = 0; i < 2 * STEPS; ++i)
-                    if (i * NKS / (2 * STEPS) == ks) store_piece(buf ^ 1, prev, i);
+                for (int i = 0; i < NST; ++i)
+                    if (i * NKS / NST == ks) store_piece(buf ^ 1, prev, i);
             }
         }
         // register r of lane (n, kk) of row tile ti: element EW w + 16 ti + 4 kk + r of slice n
@@ -404,7 +415,7 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
         products(buf, ybuf, t != (int64_t)blockIdx.x, t - gridDim.x);
         // The y tile after this one was asked for WSD_NY - 1 tiles ago.  Requests retire in order, and the younger
         // ones are the stores of WSD_NY - 1 tiles and the copies of the WSD_NY - 2 y tiles between.
-        constexpr int younger = (WSD_NY - 1) * 2 * STEPS;
+        constexpr int younger = (WSD_NY - 1) * NST;
         if (ncopy == 0) wait_vmem_at_most<younger>();
         else if (ncopy == 1) wait_vmem_at_most<younger + (WSD_NY - 2)>();
         else wait_vmem_at_most<younger + 2 * (WSD_NY - 2)>();
@@ -416,7 +427,7 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
     // the last tile's rows (its barrier has passed)
     if ((int64_t)blockIdx.x < a.ntiles) {
 #pragma unroll
-        for (int i = 0; i < 2 * STEPS; ++i) store_piece(buf ^ 1, t - gridDim.x, i);
+        for (int i = 0; i < NST; ++i) store_piece(buf ^ 1, t - gridDim.x, i);
     }
     drain_memory();   // the last copies have no reader: let them land before the buffers are used again or released
 
@@ -433,11 +444,11 @@ __global__ __launch_bounds__(512) void decompress_ws_kernel(WsdArgs a)
             if (row >= a.tail_rows) continue;
             const f4 v = *(const f4*)(os + row * RS + q * 256 + lane * 4);
             const int64_t e = (a.first + 16 * a.ntiles + row) * (int64_t)D + q * 256 + lane * 4;
-            if (e + 3 < a.M) *(f4*)(a.out + e) = v;
-            else {
-                if (e < a.M) a.out[e] = v.x;
-                if (e + 1 < a.M) a.out[e + 1] = v.y;
-                if (e + 2 < a.M) a.out[e + 2] = v.z;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (e + r >= a.M) break;
+                if constexpr (OBF) ((unsigned short*)a.out)[e + r] = (unsigned short)f32_to_bf16_rne(v[r]);
+                else ((float*)a.out)[e + r] = v[r];
             }
         }
     }
@@ -630,7 +641,7 @@ int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, 
     return exact ? compress_ws_steps<true>(h, a, st) : compress_ws_steps<false>(h, a, st);
 }
 
-template <int STEPS, int NKS, bool EXACT>
+template <int STEPS, int NKS, bool EXACT, bool OBF>
 static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
 {
     constexpr int D = 256 * STEPS;
@@ -638,42 +649,42 @@ static int launch_wsd(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
     static_assert(lds <= 160 * 1024, "LDS");
     static gvq_once_per_device once;
     if (once.first(h->device))
-        GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS, EXACT>,
+        GVQ_HIP(hipFuncSetAttribute((const void*)decompress_ws_kernel<STEPS, NKS, EXACT, OBF>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     int64_t grid = a.ntiles < h->num_cu ? a.ntiles : h->num_cu;   // one work-group per compute unit
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS, EXACT>), dim3((unsigned)grid), dim3(512), lds, st, a);
+    hipLaunchKernelGGL((decompress_ws_kernel<STEPS, NKS, EXACT, OBF>), dim3((unsigned)grid), dim3(512), lds, st, a);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
 
-template <int STEPS, bool EXACT>
+template <int STEPS, bool EXACT, bool OBF>
 static int decompress_ws_nks(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
 {
     // the shapes gvq_wsd_shape lets through: 2 STEPS x NKS <= 18, NKS <= 4
     switch (wsd_nks(h->k)) {
-    case 1: return launch_wsd<STEPS, 1, EXACT>(h, a, st);
-    case 2: return launch_wsd<STEPS, 2, EXACT>(h, a, st);
-    case 3: if constexpr (STEPS <= 3) return launch_wsd<STEPS, 3, EXACT>(h, a, st); else break;
-    case 4: if constexpr (STEPS <= 2) return launch_wsd<STEPS, 4, EXACT>(h, a, st); else break;
+    case 1: return launch_wsd<STEPS, 1, EXACT, OBF>(h, a, st);
+    case 2: return launch_wsd<STEPS, 2, EXACT, OBF>(h, a, st);
+    case 3: if constexpr (STEPS <= 3) return launch_wsd<STEPS, 3, EXACT, OBF>(h, a, st); else break;
+    case 4: if constexpr (STEPS <= 2) return launch_wsd<STEPS, 4, EXACT, OBF>(h, a, st); else break;
     }
     return GVQ_EINVAL;
 }
 
-template <bool EXACT>
+template <bool EXACT, bool OBF>
 static int decompress_ws_steps(const gvq_basis* h, const WsdArgs& a, hipStream_t st)
 {
     switch (h->d / 256) {
-    case 1: return decompress_ws_nks<1, EXACT>(h, a, st);
-    case 2: return decompress_ws_nks<2, EXACT>(h, a, st);
-    case 3: return decompress_ws_nks<3, EXACT>(h, a, st);
-    default: return decompress_ws_nks<4, EXACT>(h, a, st);
+    case 1: return decompress_ws_nks<1, EXACT, OBF>(h, a, st);
+    case 2: return decompress_ws_nks<2, EXACT, OBF>(h, a, st);
+    case 3: return decompress_ws_nks<3, EXACT, OBF>(h, a, st);
+    default: return decompress_ws_nks<4, EXACT, OBF>(h, a, st);
     }
 }
 
-// Decompresses the range into fp32 (as far as the gradient has slices); *done = the slices it took.
-int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, float* out,
-                             bool exact, hipStream_t st, int64_t* done)
+// Decompresses the range (as far as the gradient has slices) into fp32 or bf16; *done = the slices it took.
+int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, void* out,
+                             bool out_bf16, bool exact, hipStream_t st, int64_t* done)
 {
     WsdArgs a;
     const size_t copy = wsd_copy_halves(h->d, h->k);
@@ -686,5 +697,6 @@ int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t firs
     a.il = gvq_opt_interleave() > 0 ? gvq_opt_interleave() : WSD_IL;
     *done = 16 * a.ntiles + a.tail_rows;
     if (*done == 0) return GVQ_OK;
-    return exact ? decompress_ws_steps<true>(h, a, st) : decompress_ws_steps<false>(h, a, st);
+    if (out_bf16) return exact ? decompress_ws_steps<true, true>(h, a, st) : decompress_ws_steps<false, true>(h, a, st);
+    return exact ? decompress_ws_steps<true, false>(h, a, st) : decompress_ws_steps<false, false>(h, a, st);
 }

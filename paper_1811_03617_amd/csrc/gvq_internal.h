@@ -147,10 +147,10 @@ int gvq_launch_decompress_long(const gvq_basis* h, const float* comp, int64_t fi
 // of 16 whole slices.  The launcher reports the slices done (the whole range, as far as the gradient has slices).
 bool gvq_ws_shape(const gvq_basis* h);   // it can take this handle's shape
 size_t gvq_ws_pack_halves(int d, int k);   // bf16 values of its operand-order copy of U
-bool gvq_wsd_shape(const gvq_basis* h);  // the decompress kernel of the same kind (fp32 output) can take the shape
+bool gvq_wsd_shape(const gvq_basis* h);  // the decompress kernel of the same kind can take the shape
 size_t gvq_ws_alloc_halves(const gvq_basis* h);   // bf16 values of d_Uws: both kernels' copies
-int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, float* out,
-                             bool exact, hipStream_t st, int64_t* done);
+int gvq_launch_decompress_ws(const gvq_basis* h, const float* comp, int64_t first_slice, int64_t n_slices, void* out,
+                             bool out_bf16, bool exact, hipStream_t st, int64_t* done);
 int gvq_launch_pack_ws(const gvq_basis* h, hipStream_t st);
 int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, int64_t first_slice, int64_t n_slices,
                            const float* comp_in, float* out, bool exact, hipStream_t st, int64_t* done);
