@@ -920,12 +920,13 @@ int gvq_launch_compress_long(const gvq_basis* h, const void* grad, int n_workers
                              int64_t n_slices, const float* comp_in, float* out, hipStream_t st)
 {
     const bool split = gvq_long_split(h), bf = h->dtype == GVQ_BF16;
-    // fp32 gradients in the shapes it takes: the kernel that keeps U in registers (option 2 = 3: never).  With exact
+    // the shapes it takes (one basis, d a multiple of 256): the kernel that keeps U in registers (option 2 = 3: never).
+    // bf16 storage on the split pipe only.  With exact
     // fp32 products only from d = 512 up: at d = 256 its two accumulator chains per wave leave the fp32 matrix pipe
     // waiting, and the LDS-tiled kernel is 13 - 20 % faster (d = 768, k = 16: 5.2 against 4.5 TB/s; d = 1024: 5.2
     // against 3.5; d = 512: level).
     const int mode = gvq_opt_long_mode();
-    if (!bf && gvq_ws_shape(h) && mode != 3 && (split || h->d >= 512)) {
+    if (gvq_ws_shape(h) && mode != 3 && (split || (!bf && h->d >= 512))) {
         int64_t done = 0;
         const int rc = gvq_launch_compress_ws(h, grad, n_workers, first_slice, n_slices, comp_in, out, !split, st, &done);
         if (rc != GVQ_OK) return rc;

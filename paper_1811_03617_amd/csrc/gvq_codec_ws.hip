@@ -25,6 +25,8 @@
 
 #include "gvq_device.h"
 
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
 struct WsArgs {
     const void* in;          // gradient
     void* out;               // y
@@ -66,14 +68,23 @@ __device__ __forceinline__ void claim_loaded(f4& v) { asm volatile("" : "+v"(v))
 // EXACT: fp32 products on v_mfma_f32_16x16x4_f32 instead of the bf16 split; U then sits in the same registers as
 // floats (word [st][nt][h], register r: U[EW w + 32 st + 16 h + 4 kk + r][16 nt + m] for lane (m, kk)), and each of a
 // lane's 8 floats of x per step is the B operand of one product.
-template <int STEPS, int NT, bool EXACT>
+// BIN: the gradient is stored as bf16.  A tile is then 16 rows of D bf16 without padding, its 16-byte chunks
+// swizzled inside each row (chunk c of row r sits at chunk c ^ (r & 7): the copies place them so, and 8 lanes reading
+// the same chunk of 8 rows hit 8 different bank groups); a lane widens its 8 numbers to fp32 and goes on as for fp32
+// storage.  The strips of such a tile are too small for the partial results, which get a region of their own:
+// part[8][16][16 NT + 4] floats.
+template <int STEPS, int NT, bool EXACT, bool BIN>
 __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
 {
     extern __shared__ f4 smem[];
     constexpr int D = 256 * STEPS, RS = D + WS_ROWPAD, EW = 32 * STEPS;
+    constexpr int XT = BIN ? 8 * D : 16 * RS;   // floats of LDS per tile buffer
+    constexpr int PS = 16 * NT + 4;             // BIN: floats per row of a wave's partial result
+    constexpr int NCP = BIN ? STEPS : 2 * STEPS;   // 1 KB copies per wave and tile
     static_assert(16 * NT <= EW, "a wave's partial result must fit the strip of the tile it alone reads");
-    float* xs = (float*)smem;                 // [nbuf][16][RS]
-    float* mus = xs + nbuf * 16 * RS;         // [D]
+    float* xs = (float*)smem;                 // [nbuf][16][RS], or [nbuf][16][D] bf16
+    float* part = xs + nbuf * XT;             // BIN only: [8][16][PS]
+    float* mus = part + (BIN ? WS_WAVES * 16 * PS : 0);   // [D]
     const int tid = threadIdx.x, lane = tid & 63, n_ = lane & 15, kk = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
@@ -87,11 +98,18 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
     for (int e = tid; e < D; e += 512) mus[e] = a.mu[e] / a.n_workers;
 
     const unsigned int xs_off = (unsigned int)(size_t)(__attribute__((address_space(3))) void*)xs;
-    // Piece i (0 .. 2 STEPS - 1) of this wave's share of a tile: 1 KB of row 2w + i / STEPS, into buffer buf
+    // Piece i (0 .. NCP - 1) of this wave's share of a tile: 1 KB of row 2w + i / STEPS, into buffer buf; BIN: the 64
+    // chunks from chunk 64 (w STEPS + i) of the tile on, each fetched from where the swizzle says
     auto copy_piece = [&](int64_t tile, int buf, int i) {
-        const int row = 2 * w + i / STEPS, q = i % STEPS;
-        const float* g = (const float*)a.in + ((a.first + 16 * tile + row) * (int64_t)D + q * 256 + lane * 4);
-        copy_1k_to_lds(g, xs_off + 4u * (unsigned int)((buf * 16 + row) * RS + q * 256));
+        if constexpr (BIN) {
+            const int P = 64 * (w * STEPS + i) + lane, row = P / (D / 8), c = (P - row * (D / 8)) ^ (row & 7);
+            const unsigned short* g = (const unsigned short*)a.in + ((a.first + 16 * tile + row) * (int64_t)D + 8 * c);
+            copy_1k_to_lds(g, xs_off + 4u * (unsigned int)(buf * XT) + 1024u * (unsigned int)(w * STEPS + i));
+        } else {
+            const int row = 2 * w + i / STEPS, q = i % STEPS;
+            const float* g = (const float*)a.in + ((a.first + 16 * tile + row) * (int64_t)D + q * 256 + lane * 4);
+            copy_1k_to_lds(g, xs_off + 4u * (unsigned int)((buf * 16 + row) * RS + q * 256));
+        }
     };
 
     // Wave v adds up column tile v when that tile holds a comp below k; it then issues exactly one store per tile.
@@ -104,7 +122,7 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
         const int64_t tp = t + (int64_t)p * gridDim.x;
         if (tp < a.ntiles) {
 #pragma unroll
-            for (int i = 0; i < 2 * STEPS; ++i) copy_piece(tp, p, i);
+            for (int i = 0; i < NCP; ++i) copy_piece(tp, p, i);
         }
     }
     drain_memory();   // U and the first tiles have arrived: the loop below inherits no wait
@@ -123,17 +141,33 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = f4{0.f, 0.f, 0.f, 0.f};
         float* xrow = xs + (buf * 16 + n_) * RS + EW * w + 4 * kk;
+        const unsigned short* xrow16 = (const unsigned short*)(xs + buf * XT) + n_ * D;   // BIN
         const float* mrow = mus + EW * w + 4 * kk;
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) {
             // lane (n, kk): elements EW w + 32 st + 16 h + 4 kk .. + 3, h = 0, 1, of slice n
-            const f4 x0 = *(const f4*)(xrow + 32 * st), x1 = *(const f4*)(xrow + 32 * st + 16);
+            f4 x0, x1;
+            if constexpr (BIN) {
+                const int e0 = EW * w + 32 * st + 4 * kk, e1 = e0 + 16;
+                const u2 h0 = *(const u2*)(xrow16 + 8 * ((e0 >> 3) ^ (n_ & 7)) + (e0 & 4));
+                const u2 h1 = *(const u2*)(xrow16 + 8 * ((e1 >> 3) ^ (n_ & 7)) + (e1 & 4));
+                x0 = f4{__uint_as_float(h0.x << 16), __uint_as_float(h0.x & 0xffff0000u), __uint_as_float(h0.y << 16),
+                        __uint_as_float(h0.y & 0xffff0000u)};
+                x1 = f4{__uint_as_float(h1.x << 16), __uint_as_float(h1.x & 0xffff0000u), __uint_as_float(h1.y << 16),
+                        __uint_as_float(h1.y & 0xffff0000u)};
+            } else {
+                x0 = *(const f4*)(xrow + 32 * st);
+                x1 = *(const f4*)(xrow + 32 * st + 16);
+            }
             const f4 m0 = *(const f4*)(mrow + 32 * st), m1 = *(const f4*)(mrow + 32 * st + 16);
-            // two pieces of the tile ahead per step, between the products: every wave is past the second
-            // barrier of the tile that used that buffer
+            // the pieces of the tile ahead, between the products: every wave is past the second barrier of the tile
+            // that used that buffer
             if constexpr (AHEAD) {
-                copy_piece(ta, bufa, 2 * st);
-                copy_piece(ta, bufa, 2 * st + 1);
+                if constexpr (BIN) copy_piece(ta, bufa, st);
+                else {
+                    copy_piece(ta, bufa, 2 * st);
+                    copy_piece(ta, bufa, 2 * st + 1);
+                }
             }
             if constexpr (EXACT) {
                 const f4 xc[2] = {x0 - m0, x1 - m1};
@@ -162,22 +196,24 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
         }
         // The partial result goes where this wave's strip of x was: nobody else reads that strip, and this wave
         // is done with it.  Register r of lane (n, kk) of column tile nt: row n, float EW w + 16 nt + 4 kk + r.
+        float* pw = BIN ? part + (w * 16 + n_) * PS + 4 * kk : xrow;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) *(f4*)(xrow + 16 * nt) = acc[nt];
+        for (int nt = 0; nt < NT; ++nt) *(f4*)(pw + 16 * nt) = acc[nt];
         __syncthreads();
         // wave v adds the 8 partial results of column tile v (comps 16 v + 4 kk + r of slice n).  The
         // buffer is next written by the copy of a later tile, which every wave asks for after the next barrier.
         if (adds) {
-            const float* prow = xs + (buf * 16 + n_) * RS + 16 * w + 4 * kk;
+            const float* prow = BIN ? part + n_ * PS + 16 * w + 4 * kk : xs + (buf * 16 + n_) * RS + 16 * w + 4 * kk;
+            constexpr int PV = BIN ? 16 * PS : EW;   // from one wave's partial result to the next
             f4 s = *(const f4*)prow;
 #pragma unroll
-            for (int v = 1; v < WS_WAVES; ++v) s += *(const f4*)(prow + EW * v);
+            for (int v = 1; v < WS_WAVES; ++v) s += *(const f4*)(prow + PV * v);
             const int c0 = 16 * w + 4 * kk;
             const int64_t o = (a.first + 16 * tile + n_) * a.k + c0;
             float* Y = (float*)a.out;
             if (ring) {
                 // younger than the word asked for: this tile's copies
-                if constexpr (AHEAD) wait_vmem_at_most<2 * STEPS>(); else wait_vmem_at_most<0>();
+                if constexpr (AHEAD) wait_vmem_at_most<NCP>(); else wait_vmem_at_most<0>();
                 claim_loaded(prev);
                 s += prev;
             }
@@ -191,12 +227,12 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
         const int64_t ta = t + (int64_t)ahead * gridDim.x < a.ntiles ? t + (int64_t)ahead * gridDim.x : t;
         const int bufa = buf == 0 ? nbuf - 1 : buf - 1;
         // This wave's rows of the current tile: memory operations retire in order, and the requests younger
-        // than them are the copies of the tiles between (2 STEPS each) and one store per tile for the waves
+        // than them are the copies of the tiles between (NCP each) and one store per tile for the waves
         // that add up a column tile.
         if (ahead == 2) {
-            if (adds && ring) wait_vmem_at_most<2 * STEPS + 3>();   // ... and the word of the partial sum in between
-            else if (adds) wait_vmem_at_most<2 * STEPS + 2>();
-            else wait_vmem_at_most<2 * STEPS>();
+            if (adds && ring) wait_vmem_at_most<NCP + 3>();   // ... and the word of the partial sum in between
+            else if (adds) wait_vmem_at_most<NCP + 2>();
+            else wait_vmem_at_most<NCP>();
         } else {
             if (adds) wait_vmem_at_most<1>(); else wait_vmem_at_most<0>();
         }
@@ -210,6 +246,21 @@ __global__ __launch_bounds__(512) void compress_ws_kernel(WsArgs a, int nbuf)
     if (a.tail_rows > 0 && (int64_t)blockIdx.x == a.ntiles % gridDim.x) {
         __syncthreads();   // every wave has read its last partial results
         const int64_t s0 = a.first + 16 * a.ntiles;
+        if constexpr (BIN) {
+            const unsigned short* in16 = (const unsigned short*)a.in;
+            for (int P = tid; P < 2 * D; P += 512) {   // the tile's 16-byte chunks, in LDS order
+                const int row = P / (D / 8), c = (P - row * (D / 8)) ^ (row & 7);
+                const int64_t e = (s0 + row) * (int64_t)D + 8 * c;
+                unsigned int hw[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+                if (row < a.tail_rows) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (e + i < a.M) hw[i] = in16[e + i];
+                }
+                *(u4*)((unsigned short*)xs + 8 * P) = u4{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16),
+                                                        hw[6] | (hw[7] << 16)};
+            }
+        } else
         for (int i = tid; i < 16 * (D / 4); i += 512) {
             const int row = i / (D / 4), c4 = i - row * (D / 4);
             const int64_t e = (s0 + row) * (int64_t)D + 4 * c4;
@@ -515,7 +566,11 @@ __global__ void pack_ws_exact_kernel(const float* U, float* Ue, int d, int k, in
 static int ws_nt(int k) { const int nt = (k + 15) / 16; return nt + (nt & 1); }   // column tiles, even
 
 // LDS: nbuf tiles of 16 padded rows, and mu
-static size_t ws_lds(int d, int nbuf) { return sizeof(float) * ((size_t)nbuf * 16 * (d + WS_ROWPAD) + d); }
+static size_t ws_lds(int d, int nbuf, bool bin = false, int nt = 0)
+{
+    if (bin) return sizeof(float) * ((size_t)nbuf * 8 * d + (size_t)WS_WAVES * 16 * (16 * nt + 4) + d);
+    return sizeof(float) * ((size_t)nbuf * 16 * (d + WS_ROWPAD) + d);
+}
 // Tiles of x in LDS: three (two in flight) where they fit 160 KB (d <= 768), else two (with two, d = 256 is 20 %
 // slower, d = 768 2 %; d = 512 measures 3 % faster, within what one box differs from the next)
 static int ws_nbuf(int d) { return ws_lds(d, 3) <= 160 * 1024 ? 3 : 2; }
@@ -593,33 +648,33 @@ static int launch_ws(const gvq_basis* h, const WsArgs& a, size_t lds, int nbuf, 
     return GVQ_OK;
 }
 
-template <int STEPS, bool EXACT>
+template <int STEPS, bool EXACT, bool BIN>
 static int compress_ws_nt(const gvq_basis* h, const WsArgs& a, hipStream_t st)
 {
-    const int NT = ws_nt(h->k), nbuf = ws_nbuf(256 * STEPS);
-    const size_t lds = ws_lds(256 * STEPS, nbuf);
+    const int NT = ws_nt(h->k), nbuf = BIN ? 3 : ws_nbuf(256 * STEPS);
+    const size_t lds = ws_lds(256 * STEPS, nbuf, BIN, NT);
     // the shapes gvq_ws_shape lets through: 16 NT <= 32 STEPS, and STEPS x NT <= 18
     if constexpr (STEPS == 4) {
-        if (NT == 4) return launch_ws<compress_ws_kernel<4, 4, EXACT>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<4, 4, EXACT, BIN>>(h, a, lds, nbuf, st);
     }
     if constexpr (STEPS == 3) {
-        if (NT == 6) return launch_ws<compress_ws_kernel<3, 6, EXACT>>(h, a, lds, nbuf, st);
-        if (NT == 4) return launch_ws<compress_ws_kernel<3, 4, EXACT>>(h, a, lds, nbuf, st);
+        if (NT == 6) return launch_ws<compress_ws_kernel<3, 6, EXACT, BIN>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<3, 4, EXACT, BIN>>(h, a, lds, nbuf, st);
     }
     if constexpr (STEPS == 2) {
-        if (NT == 4) return launch_ws<compress_ws_kernel<2, 4, EXACT>>(h, a, lds, nbuf, st);
+        if (NT == 4) return launch_ws<compress_ws_kernel<2, 4, EXACT, BIN>>(h, a, lds, nbuf, st);
     }
-    return launch_ws<compress_ws_kernel<STEPS, 2, EXACT>>(h, a, lds, nbuf, st);
+    return launch_ws<compress_ws_kernel<STEPS, 2, EXACT, BIN>>(h, a, lds, nbuf, st);
 }
 
-template <bool EXACT>
+template <bool EXACT, bool BIN>
 static int compress_ws_steps(const gvq_basis* h, const WsArgs& a, hipStream_t st)
 {
     switch (h->d / 256) {
-    case 1: return compress_ws_nt<1, EXACT>(h, a, st);
-    case 2: return compress_ws_nt<2, EXACT>(h, a, st);
-    case 3: return compress_ws_nt<3, EXACT>(h, a, st);
-    default: return compress_ws_nt<4, EXACT>(h, a, st);
+    case 1: return compress_ws_nt<1, EXACT, BIN>(h, a, st);
+    case 2: return compress_ws_nt<2, EXACT, BIN>(h, a, st);
+    case 3: return compress_ws_nt<3, EXACT, BIN>(h, a, st);
+    default: return compress_ws_nt<4, EXACT, BIN>(h, a, st);
     }
 }
 
@@ -638,7 +693,8 @@ int gvq_launch_compress_ws(const gvq_basis* h, const void* grad, int n_workers, 
     a.tail_rows = tail > 0 ? (int)tail : 0;
     *done = 16 * a.ntiles + a.tail_rows;
     if (*done == 0) return GVQ_OK;
-    return exact ? compress_ws_steps<true>(h, a, st) : compress_ws_steps<false>(h, a, st);
+    if (h->dtype == GVQ_BF16) return exact ? GVQ_EINVAL : compress_ws_steps<false, true>(h, a, st);   // bf16 storage: split pipe only
+    return exact ? compress_ws_steps<true, false>(h, a, st) : compress_ws_steps<false, false>(h, a, st);
 }
 
 template <int STEPS, int NKS, bool EXACT, bool OBF>

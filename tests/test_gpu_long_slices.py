@@ -266,6 +266,20 @@ def test_basis_stationary_kernels_with_several_tiles_per_work_group(M, d, k):
     _check_codec(_wl(M, d, k, 1, 2), out_dtype="bf16", fit=False)   # fp32 output, and bf16 output from the same sum
 
 
+@pytest.mark.parametrize("M,d,k,fit", [
+    (768 * 300 + 9, 768, 96, True),
+    (256 * 500 + 3, 256, 32, True),
+    (1024 * 60 + 5, 1024, 64, True),
+    (512 * 100, 512, 52, True),
+    (768 * 20 + 5, 768, 96, True),                       # one whole tile and a tail that ends after 5 elements
+    (768 * (16 * 256 * 5 + 11) + 100, 768, 96, False),   # five tiles per work-group
+])
+def test_basis_stationary_kernels_on_bf16_storage(M, d, k, fit):
+    """bf16 gradients: the tile sits in LDS as bf16 with swizzled 16-byte chunks and the partial results in a region
+    of their own; decompress rounds to bf16 at its row stores.  Same oracle comparison as for fp32 storage."""
+    _check_codec(_wl(M, d, k, 2, 2, dtype="bf16"), out_dtype="bf16", fit=fit)
+
+
 def test_pipe_option_range():
     assert gvq.lib().gvq_set_option(2, 4) == gvq.EINVAL
     assert gvq.lib().gvq_set_option(2, 0) == gvq.OK
