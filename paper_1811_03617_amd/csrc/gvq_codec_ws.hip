@@ -1,5 +1,6 @@
-// Basis-stationary kernels for long slices (Section 3, "slice size": d = 768 in the paper's example) on
-// the bf16 matrix pipe: Eq. (2), y = U^T (x - mu/N), first; Eq. (4) further down.
+// Basis-stationary kernels for long slices (Section 3, "slice size": d = 768 in the paper's example):
+// Eq. (2), y = U^T (x - mu/N), first; Eq. (4) further down.  Products on the bf16 matrix pipe (two-term split) or,
+// EXACT, on the fp32 one; fp32 or bf16 storage.
 //
 // The LDS-tiled kernels of gvq_codec_long.hip stream U through LDS once per 128-slice tile and walk over the
 // gradient in 256-byte strips of 128 rows.  Here the roles are swapped.  A compute unit's register files hold
@@ -13,8 +14,7 @@
 // 8 partial results meet in LDS, each in the strip of the tile that its wave alone reads, and are added.
 //
 // Products as in the split kernels: a = a1 + a2 in bf16, x u = x1 u1 + x1 u2 + x2 u1 with fp32 accumulation on
-// v_mfma_f32_16x16x32_bf16.  Shapes: fp32 gradients, one basis, d a multiple of 256, k of 4, and the limits of
-// gvq_ws_shape.  The slices after the last whole 16-slice tile of a range (and the slice that ends past the gradient's
+// v_mfma_f32_16x16x32_bf16.  Shapes: one basis, d a multiple of 256, k of 4, and the limits of gvq_ws_shape.  The slices after the last whole 16-slice tile of a range (and the slice that ends past the gradient's
 // end) are one more tile, fetched with bounds-checked loads by one work-group: a second launch for them would cost a
 // fifth of the whole kernel's time (one work-group of the LDS-tiled kernel walking through all of U: 33 us).
 // Eq. (4) has a kernel of the same kind further down (decompress_ws_kernel): there a wave owns an eighth of the
@@ -63,7 +63,8 @@ __device__ __forceinline__ void load_uncounted(f4& v, const float* p)
 __device__ __forceinline__ void claim_loaded(f4& v) { asm volatile("" : "+v"(v)); }
 
 // --------------------------------------------------------------------------------------
-// compress.  LDS: xs[2][16][d + 4] floats, part[8][NT][64] 128-bit words, mus[d] floats.
+// compress.  LDS: xs[nbuf][16][d + 4] floats (the partial results reuse the strips of the tile), mus[d] floats; for
+// bf16 storage see BIN below.
 // --------------------------------------------------------------------------------------
 // EXACT: fp32 products on v_mfma_f32_16x16x4_f32 instead of the bf16 split; U then sits in the same registers as
 // floats (word [st][nt][h], register r: U[EW w + 32 st + 16 h + 4 kk + r][16 nt + m] for lane (m, kk)), and each of a
