@@ -123,6 +123,13 @@ def run_workload(name, args):
         if events is not None:
             events[3].record()
 
+    # The GPU takes its time to settle on its clocks after the idle moments of set-up: a quarter of a second of the
+    # same work first (untimed, whatever --warmup says), so that a short run measures the same machine as a long one.
+    settle_until = time.perf_counter() + 0.25
+    while time.perf_counter() < settle_until:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
