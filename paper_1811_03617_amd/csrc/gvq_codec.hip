@@ -1579,7 +1579,7 @@ static int launch_compress_y(const gvq_basis* h, const CodecArgs& a, hipStream_t
     b.pace = pace_of(fs);
     b.run_tiles = run_length(h, a.n_super, grid, fs.many_run);
     b.rest_run = run_length(h, work_items(a) - a.n_super, grid);
-    b.il = interleave_of(b, D == 128 ? 64 : 1);   // d = 128: 5.90 -> 5.97 TB/s; no gain at d = 64
+    b.il = interleave_of(b, D >= 64 ? 64 : 1);   // steady state: d = 128 5.90 -> 5.99 TB/s, d = 64 6.09 -> 6.18, d = 32 5.43 -> 5.35
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WG_THREADS), 0, st, b);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
