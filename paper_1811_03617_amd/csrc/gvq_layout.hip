@@ -67,14 +67,17 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_kernel(LayoutArgs 
 // g = hw * nd + dd the position inside the tile and f fastest (row stride TF + V elements: 128-bit rows, and 8 lanes x
 // 128 bits cover all banks).  On the [F][D][H][W] side a thread moves V consecutive numbers of one filter's run (and
 // scatters them to, or gathers them from, V rows of the tile); on the flat side a thread moves V adjacent filters of
-// one row.
+// one row.  A tile is TD depths x all H*W positions, or, when H*W alone is longer than a tile (and a multiple of V),
+// one depth x a piece of H*W; either way a filter's part of it is one contiguous run.
 #define LF_BYTES 32768          // LDS per work-group
 
 struct LayoutFastArgs {
     const void* src;
     void* dst;
-    int F, D, HW, TD;           // TD * HW is a multiple of V and at most LF_BYTES / sizeof(T) / (TF + V)
+    int F, D, HW, TD;           // TD * HWT is a multiple of V and at most LF_BYTES / sizeof(T) / (TF + V)
     int n_dtiles;
+    int HWT, n_hwtiles;         // positions per tile: H*W (one tile over them), or a multiple of V when H*W is too long
+                                // for one tile (then TD = 1)
 };
 
 typedef unsigned int lu4 __attribute__((ext_vector_type(4)));
@@ -88,11 +91,13 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_fast_kernel(Layout
     constexpr int V = 16 / sizeof(T), RS = TF + V, QF = TF / V, ROWS = LAYOUT_THREADS / QF;
     union Vec { lu4 v; T e[V]; };
     const int tid = threadIdx.x;
-    const int ft = blockIdx.x / a.n_dtiles, dt = blockIdx.x % a.n_dtiles;
-    const int f0 = ft * TF, d0 = dt * a.TD;
+    const int ht = blockIdx.x % a.n_hwtiles, fd = blockIdx.x / a.n_hwtiles;
+    const int ft = fd / a.n_dtiles, dt = fd % a.n_dtiles;
+    const int f0 = ft * TF, d0 = dt * a.TD, hw0 = ht * a.HWT;
     const int nf = a.F - f0 < TF ? a.F - f0 : TF;             // a multiple of V
     const int nd = a.D - d0 < a.TD ? a.D - d0 : a.TD;
-    const int run = nd * a.HW, rq = run / V;                 // run: a multiple of V, rq <= 32
+    const int nhw = a.HW - hw0 < a.HWT ? a.HW - hw0 : a.HWT;
+    const int run = nd * nhw, rq = run / V;                  // run: a multiple of V, contiguous in a filter (nd = 1 or nhw = H*W)
     const T* grad = (const T*)(FLATTEN ? a.src : a.dst);
     const T* flat = (const T*)(FLATTEN ? a.dst : a.src);
     // the [F][D][H][W] side: this thread's chunk c of a run, for filters fsub, fsub + fpp, ...
@@ -100,16 +105,16 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_fast_kernel(Layout
     int g[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-        const int r = V * c + i, dd = r / a.HW, hw = r - dd * a.HW;
+        const int r = V * c + i, dd = r / nhw, hw = r - dd * nhw;
         g[i] = (hw * nd + dd) * RS;
     }
     // the flat side: V adjacent filters q of rows gr, gr + ROWS, ...
     const int q = tid % QF, gr = tid / QF;
-    auto grad_ptr = [&](int f) { return (T*)grad + ((size_t)(f0 + f) * a.D + d0) * a.HW + V * c; };
+    auto grad_ptr = [&](int f) { return (T*)grad + ((size_t)(f0 + f) * a.D + d0) * a.HW + hw0 + V * c; };
     auto flat_rows = [&](auto&& body) {
         int hw = gr / nd, dd = gr - hw * nd;
         for (int gg = gr; gg < run; gg += ROWS) {
-            if (V * q < nf) body(gg, (T*)flat + ((size_t)hw * a.D + d0 + dd) * a.F + f0 + V * q);
+            if (V * q < nf) body(gg, (T*)flat + ((size_t)(hw0 + hw) * a.D + d0 + dd) * a.F + f0 + V * q);
             dd += ROWS;
             while (dd >= nd) { dd -= nd; ++hw; }
         }
@@ -137,10 +142,17 @@ __global__ __launch_bounds__(LAYOUT_THREADS) void conv_layout_fast_kernel(Layout
     }
 }
 
-// Depths per tile for the kernel above with at most max_run rows, or 0 when the shape does not fit it.
-static int layout_fast_td(const void* src, const void* dst, int F, int D, int HW, int V, int max_run)
+// Depths per tile for the kernel above with at most max_run rows (a multiple of V), or 0 when the shape does not fit
+// it; *hwt: the positions per tile.
+static int layout_fast_td(const void* src, const void* dst, int F, int D, int HW, int V, int max_run, int* hwt)
 {
-    if ((((uintptr_t)src | (uintptr_t)dst) & 15) || F % V || ((int64_t)D * HW) % V || HW > max_run) return 0;
+    *hwt = HW;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15) || F % V || ((int64_t)D * HW) % V) return 0;
+    if (HW > max_run) {   // one depth per tile, H*W in pieces
+        if (HW % V) return 0;
+        *hwt = max_run;
+        return 1;
+    }
     int step = V;                                  // TD * HW must be a multiple of V: TD of V / gcd(HW, V)
     while (step > 1 && (HW * (step / 2)) % V == 0) step /= 2;
     int td = max_run / HW / step * step;
@@ -150,20 +162,23 @@ static int layout_fast_td(const void* src, const void* dst, int F, int D, int HW
 }
 
 template <typename T, bool FLATTEN, int TF>
-static int launch_layout_fast(const void* src, void* dst, int F, int D, int HW, int td, hipStream_t st)
+static int launch_layout_fast(const void* src, void* dst, int F, int D, int HW, int td, int hwt, hipStream_t st)
 {
     LayoutFastArgs a;
     a.src = src; a.dst = dst; a.F = F; a.D = D; a.HW = HW; a.TD = td;
     a.n_dtiles = (D + td - 1) / td;
+    a.HWT = hwt; a.n_hwtiles = (HW + hwt - 1) / hwt;
     const int n_ftiles = (F + TF - 1) / TF;
-    const size_t lds = sizeof(T) * (size_t)td * HW * (TF + 16 / sizeof(T));
-    hipLaunchKernelGGL((conv_layout_fast_kernel<T, FLATTEN, TF>), dim3(n_ftiles * a.n_dtiles), dim3(LAYOUT_THREADS), lds,
+    const size_t lds = sizeof(T) * (size_t)td * hwt * (TF + 16 / sizeof(T));
+    const int64_t grid = (int64_t)n_ftiles * a.n_dtiles * a.n_hwtiles;
+    if (grid > 0x7fffffff) return GVQ_EINVAL;
+    hipLaunchKernelGGL((conv_layout_fast_kernel<T, FLATTEN, TF>), dim3((unsigned)grid), dim3(LAYOUT_THREADS), lds,
                        st, a);
     GVQ_HIP(hipGetLastError());
     return GVQ_OK;
 }
 
-// H*W too large for an LDS tile: one thread per number (correct, not fast).
+// H*W too large for an LDS tile and not a multiple of the vector width: one thread per number (correct, not fast).
 template <typename T, bool FLATTEN>
 __global__ void conv_layout_direct_kernel(const T* src, T* dst, int F, int D, int HW)
 {
@@ -186,10 +201,11 @@ static int launch_layout(const void* src, void* dst, int F, int D, int HW, hipSt
         // fp32 unflatten, 128 is 15 - 30 % slower)
         constexpr int V = 16 / sizeof(T);
         const int tf = HW == 1 && F >= 128 && (FLATTEN || sizeof(T) == 2) ? 128 : 64;
-        const int td = layout_fast_td(src, dst, F, D, HW, V, LF_BYTES / (int)sizeof(T) / (tf + V) / V * V);
+        int hwt = HW;
+        const int td = layout_fast_td(src, dst, F, D, HW, V, LF_BYTES / (int)sizeof(T) / (tf + V) / V * V, &hwt);
         if (td > 0) {
-            if (tf == 128) return launch_layout_fast<T, FLATTEN, 128>(src, dst, F, D, HW, td, st);
-            return launch_layout_fast<T, FLATTEN, 64>(src, dst, F, D, HW, td, st);
+            if (tf == 128) return launch_layout_fast<T, FLATTEN, 128>(src, dst, F, D, HW, td, hwt, st);
+            return launch_layout_fast<T, FLATTEN, 64>(src, dst, F, D, HW, td, hwt, st);
         }
     }
     if ((int64_t)LAYOUT_TF * HW > LAYOUT_LDS_ELEMS) {

@@ -22,6 +22,7 @@ SHAPES = [
     # a fully connected layer (a plain transpose), H*W = 49 with 4 depths per tile, F below one tile
     (68, 36, 3, 3), (64, 28, 5, 5), (128, 4, 3, 3), (1000, 4096, 1, 1), (128, 8, 7, 7), (4, 240, 1, 1), (8, 484, 1, 1),
     (72, 40, 5, 5), (200, 24, 3, 3), (8, 16, 2, 2),   # ... and multiples of 8 for bf16
+    (16, 8, 16, 16), (72, 3, 16, 24), (64, 5, 12, 12),   # H*W longer than a tile: one depth per tile, H*W in pieces
 ]
 
 
