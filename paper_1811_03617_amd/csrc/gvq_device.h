@@ -46,6 +46,9 @@ struct CodecArgs {
                               // super-tile p of a group is row r il + p % il of the group's il times as many rows), so that
                               // consecutive waves, which take consecutive super-tiles, read and write one compact window of
                               // memory at any moment; 1 = none (a super-tile is 2048 consecutive elements).  Whole groups only.
+    int keep_y;               // compress: the launcher picks the kernel whose fast phase writes the results with ordinary
+                              // stores (they stay in the last-level cache for whoever reads them next) instead of
+                              // non-temporal ones
     int pace;                 // fast phase: bit 0 = wait for all memory work before a super-tile is parked,
                               // bit 1 = also after its matrix products (fewer requests in flight per wave), bit 2 = the matrix
                               // products of a super-tile wait for the next one's loads one by one

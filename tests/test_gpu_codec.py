@@ -266,6 +266,36 @@ def test_row_interleave_of_the_register_resident_kernels_changes_no_bit(M, d, k,
         assert gvq.lib().gvq_set_option(5, 0) == gvq.OK
 
 
+@pytest.mark.parametrize("M,d,k", [
+    (128 * 5000 + 40, 128, 32), (128 * 5000 + 40, 128, 16), (64 * 9000 + 6, 64, 16), (32 * 20000 + 8, 32, 8),
+    (16 * 30000 + 3, 16, 4),
+])
+def test_cache_resident_and_streaming_result_stores_give_the_same_bits(M, d, k):
+    """When the n_workers results that are summed next fit the last-level cache together, compress writes them with
+    ordinary stores, otherwise with non-temporal ones (two kernel variants).  With a zero mean Eq. 2 does not depend
+    on n_workers, so a worker count on either side of that limit must give the same bits, and those of the oracle
+    to the usual tolerance."""
+    w = _wl(M, d, k, 1)
+    rng = np.random.default_rng(5)
+    U = np.linalg.qr(rng.standard_normal((d, k)))[0][None].astype(np.float32)
+    mu = np.zeros((1, d), np.float32)
+    g = synth.worker_gradients(w, "cpu")[0]
+    b = gvq.Basis(M, d, k, None, "f32")
+    b.import_(U, mu)
+    many = (224 << 20) // (b.S * k * 4) + 2
+    gd = g.to(DEV)
+    ys = []
+    for n in (1, many):
+        c = torch.full((b.S * k,), float("nan"), device=DEV)
+        b.compress(gd, n, c)
+        torch.cuda.synchronize()
+        ys.append(c.cpu().numpy().reshape(b.S, k))
+    b.close()
+    assert np.array_equal(ys[0], ys[1])
+    ref = oracle.compress(synth.to_numpy(g), U.astype(np.float64), mu.astype(np.float64), many)
+    assert_close(ys[1], ref, REL_TOL, "compress with streaming stores")
+
+
 def test_codec_is_bitwise_reproducible():
     w = _wl(128 * 2000 + 40, 128, 32, 3)
     U32, mu32 = _oracle_basis(w)
