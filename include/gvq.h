@@ -125,7 +125,10 @@ int gvq_fit_status(const gvq_basis_t* h, int* max_sweeps, void* stream);
  * (device, M elements of the handle's dtype), b the basis of slice j, the tail slice
  * zero-padded.  comp_out: device float [S][k].  n_workers >= 1 must equal the number of
  * vectors later summed by gvq_aggregate (only then do the mu/N terms add up to mu, Eq. 3);
- * the library cannot check this.  fp32 arithmetic, fp32 accumulation.
+ * the library cannot check this.  fp32 arithmetic, fp32 accumulation.  n_workers also sets the
+ * cache policy of comp_out: when n_workers vectors of S*k floats fit the last-level cache together
+ * (224 MB), comp_out is written so that it stays there for the sum that follows, otherwise with
+ * non-temporal stores; the values are the same either way.
  */
 int gvq_compress(const gvq_basis_t* h, const void* grad, int n_workers, float* comp_out,
                  void* stream);
