@@ -92,6 +92,8 @@ def run_workload(name, args):
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
+    first_slice_ms = select_k_ms = ks = None
+
     # ---- basis refresh (timed on its own) -----------------------------------------------
     if args.skip_fit:
         rng = np.random.default_rng(w.seed)
@@ -107,6 +109,24 @@ def run_workload(name, args):
         e1.record()
         torch.cuda.synchronize()
         fit_ms = e0.elapsed_time(e1)
+        if not args.no_next_rows:
+            # Section 3's own sampling: the basis of every block from the L samples of its first slice (L < d here:
+            # the L x L sample-Gram route); then the pooled fit again, untimed, so that the steps run on its basis
+            basis.fit(fit_grads, first_slice_only=True)
+            e0, e1 = ev(), ev()
+            e0.record()
+            basis.fit(fit_grads, first_slice_only=True)
+            e1.record()
+            torch.cuda.synchronize()
+            first_slice_ms = e0.elapsed_time(e1)
+            basis.fit(fit_grads)
+            torch.cuda.synchronize()
+            # Eq. 5: the smallest k per basis whose leading eigenvalues hold 1 - lambda of the total (lambda = 0.01 as
+            # in Section 4), from the eigenvalues on the device; the time includes the copy of the B results
+            basis.select_k(0.01)
+            t0 = time.perf_counter()
+            ks = basis.select_k(0.01)
+            select_k_ms = (time.perf_counter() - t0) * 1e3
     del fit_grads
 
     def step(events=None):
@@ -281,6 +301,10 @@ def run_workload(name, args):
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                       "frac": round(fit_in_bytes / fit_ms / 1e6 / HBM_PEAK_GBS, 4),
                                       "note": "whole refresh (moments + eigensolver) against the input bytes"}
+        if first_slice_ms is not None:
+            res["fit"]["first_slice_sampling_ms"] = round(first_slice_ms, 3)
+            res["fit"]["select_k"] = {"lambda": 0.01, "ms": round(select_k_ms, 3),
+                                      "k_min": int(min(ks)), "k_max": int(max(ks))}
     # slices longer than 128 elements multiply on the bf16 matrix pipe (three products of bf16 terms per
     # fp32 product): should that ever take longer at its peak than the bytes take at the HBM peak, the
     # pipe is the roofline
