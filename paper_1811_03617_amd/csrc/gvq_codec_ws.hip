@@ -48,11 +48,16 @@ struct WsArgs {
 // byte offset of the first lane's bytes inside the work-group's LDS.  Written as inline assembly so
 // that the compiler does not pair the copy with the LDS reads of the *other* buffer (it would wait
 // for the copy before every such read).
+// (m0 carries the LDS offset and is named as clobbered on purpose; the compiler remarks on every instance that m0 is
+// a reserved register, which it sets itself right before each of its own uses.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void copy_1k_to_lds(const void* src_lane, unsigned int lds_off)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src_lane), "s"(lds_off)
                  : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // 128 bits global -> registers that the compiler does not count either (it would wait for every copy in flight before
 // the first use): the caller waits by hand and then passes the value through claim_loaded before using it.
