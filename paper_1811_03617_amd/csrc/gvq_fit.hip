@@ -712,7 +712,7 @@ __global__ __launch_bounds__(1024) void gram_eigen_kernel(GramArgs a)
     for (int col = 0; col < k; ++col) {
         double* w = Uw + (size_t)col * d;
         const bool determined = col < L && lam[order[col]] > 1e-12 * top;   // uniform
-        for (int attempt = 0;; ++attempt) {
+        for (;;) {   // ends: every retry takes a new unit vector, and there are d of them
             if (!determined) {
                 for (int e = tid; e < d; e += nth) w[e] = e == next_unit ? 1.0 : 0.0;
                 ++next_unit;
