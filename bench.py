@@ -60,7 +60,7 @@ def main():
     for o in args.option:
         index, value = (int(v) for v in o.split("="))
         gvq.gvq_set_option(index, value)
-    # "all": one JSON line per workload (the table of the design doc from one command); the default is the
+    # "all": one JSON line per workload (the whole table of measurements from one command); the default is the
     # headline workload alone, ONE line
     names = list(WORKLOADS) if args.workload == "all" else [args.workload]
     for name in names:
