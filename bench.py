@@ -41,8 +41,9 @@ def main():
                     help="import a seeded random orthonormal basis instead of fitting one (counter runs: the "
                          "long-slice fit enqueues tens of thousands of small kernels)")
     ap.add_argument("--no-next-rows", action="store_true",
-                    help="leave out the timings of the ring step, the monitor and flatten (profiler runs: their "
-                         "launches would mix with those of the timed steps in per-kernel statistics)")
+                    help="leave out the timings of the ring step, the monitor, flatten, the first-slice-sampling fit "
+                         "and the rank selection (profiler runs: their launches would mix with those of the timed steps "
+                         "and of the pooled fit in per-kernel statistics)")
     ap.add_argument("--option", action="append", default=[], metavar="INDEX=VALUE",
                     help="gvq_set_option(INDEX, VALUE) before the run (launch tuning, for A/B timings); repeatable")
     args = ap.parse_args()
